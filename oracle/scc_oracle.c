@@ -1,0 +1,170 @@
+/*
+ * CPU oracle for the sliding-channel convolution (SCC) of DSXplore.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain definition the GPU
+ * library is checked against.  Only the test-suite, the smoke entry and the
+ * benchmark's cpu_baseline leg may build or call it; the product library
+ * neither links nor imports it, and the two share no code.
+ *
+ * Everything is fp64: inputs arrive already widened to double, every sum is
+ * accumulated in double, outputs are double.  Loops follow the definition
+ * directly: no blocking, no fusion, no reordering beyond "parallel over
+ * independent outputs".
+ *
+ * Passages followed:
+ *   window sequence   - Algorithm 1 ("Compute channel indexes of one cycle")
+ *                       continued past one cycle the way Algorithm 2 does
+ *                       (filter k uses entry k mod cyclic_dist, i.e. the same
+ *                       sequence simply keeps going);
+ *   forward           - Section 4.2 "Output-Centric Forward Pass": each output
+ *                       pixel is a dot product of the filter's weights with the
+ *                       pixels at the same (x, y) across the window's channels;
+ *   grad-input        - Section 4.2 "Input-Centric Backward Pass": each input
+ *                       gradient pixel pulls from the output gradients of all
+ *                       filters whose window covers its channel;
+ *   grad-weight       - Section 4.2 names the gradient of the trainable weights
+ *                       without describing a kernel; it is the derivative of
+ *                       the forward definition with respect to w.
+ *
+ * Readings taken where the paper is silent:
+ *   - overlap in channels is int(co * group_width) with C truncation of the
+ *     double product, as Algorithm 1 writes it;
+ *   - weight j of filter k multiplies the j-th channel of the window counted
+ *     from the window start, wrapping past the last channel to channel 0;
+ *   - Cin must be divisible by cg.
+ *
+ * Layout: x[N][Cin][HW], y[N][Cout][HW], w[Cout][L], all dense row-major.
+ *
+ * Pinning status (tests/test_oracle_pins.py): every function here is pinned
+ * against the paper's worked example, library convolutions for the special
+ * cases, the channel-stack composition, dense brute force, invariants and
+ * finite differences.  Nothing in this file is "parity unpinned".
+ */
+#include <stddef.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+/* Number of host threads the parallel loops below will use. */
+int scc_oracle_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+/* Window length and the channel overlap of adjacent filters (Algorithm 1:
+ * group_width = Cin // cg; the step between virtual starts is
+ * group_width - int(overlap * group_width)).  Returns 0, or -1 when the
+ * arguments do not describe an SCC layer. */
+int scc_oracle_window(int Cin, int cg, double co, int *L_out, int *ov_out)
+{
+    if (Cin <= 0 || cg <= 0 || Cin % cg != 0) return -1;
+    if (!(co >= 0.0 && co <= 1.0)) return -1;
+    int L = Cin / cg;
+    int ov = (int)(co * (double)L);
+    *L_out = L;
+    *ov_out = ov;
+    return 0;
+}
+
+/* Window start of every filter, produced by walking Algorithm 1's virtual
+ * (start_v, end_v) pair filter by filter and reducing modulo Cin.  The
+ * dictionary of Algorithm 1 only detects the period; Algorithm 2 indexes it
+ * with k mod cyclic_dist, which reproduces this same walk. */
+int scc_oracle_starts(int Cin, int Cout, int cg, double co, int *start)
+{
+    int L, ov;
+    if (scc_oracle_window(Cin, cg, co, &L, &ov) != 0 || Cout <= 0) return -1;
+    long long start_v = 0, end_v = L;
+    for (int k = 0; k < Cout; ++k) {
+        start[k] = (int)(start_v % Cin);
+        start_v = end_v - ov;
+        end_v = start_v + L;
+    }
+    return 0;
+}
+
+/* y[n,k,p] = sum_j w[k,j] * x[n, (s_k + j) mod Cin, p] */
+int scc_oracle_forward(const double *x, const double *w, double *y,
+                       int N, int Cin, int Cout, int HW, int cg, double co)
+{
+    int L, ov;
+    if (scc_oracle_window(Cin, cg, co, &L, &ov) != 0) return -1;
+    int *s = (int *)malloc(sizeof(int) * (size_t)Cout);
+    if (!s) return -2;
+    scc_oracle_starts(Cin, Cout, cg, co, s);
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int n = 0; n < N; ++n) {
+        for (int k = 0; k < Cout; ++k) {
+            double *yo = y + ((size_t)n * Cout + k) * HW;
+            for (int p = 0; p < HW; ++p) yo[p] = 0.0;
+            for (int j = 0; j < L; ++j) {
+                int c = (s[k] + j) % Cin;
+                const double *xi = x + ((size_t)n * Cin + c) * HW;
+                double wkj = w[(size_t)k * L + j];
+                for (int p = 0; p < HW; ++p) yo[p] += wkj * xi[p];
+            }
+        }
+    }
+    free(s);
+    return 0;
+}
+
+/* dx[n,c,p] = sum over filters k whose window covers c of
+ *             w[k, (c - s_k) mod Cin] * dy[n,k,p]                       */
+int scc_oracle_backward_input(const double *dy, const double *w, double *dx,
+                              int N, int Cin, int Cout, int HW, int cg, double co)
+{
+    int L, ov;
+    if (scc_oracle_window(Cin, cg, co, &L, &ov) != 0) return -1;
+    int *s = (int *)malloc(sizeof(int) * (size_t)Cout);
+    if (!s) return -2;
+    scc_oracle_starts(Cin, Cout, cg, co, s);
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int n = 0; n < N; ++n) {
+        for (int c = 0; c < Cin; ++c) {
+            double *di = dx + ((size_t)n * Cin + c) * HW;
+            for (int p = 0; p < HW; ++p) di[p] = 0.0;
+            for (int k = 0; k < Cout; ++k) {
+                int j = ((c - s[k]) % Cin + Cin) % Cin; /* position of c in window k */
+                if (j >= L) continue;                   /* window k does not cover c */
+                const double *go = dy + ((size_t)n * Cout + k) * HW;
+                double wkj = w[(size_t)k * L + j];
+                for (int p = 0; p < HW; ++p) di[p] += wkj * go[p];
+            }
+        }
+    }
+    free(s);
+    return 0;
+}
+
+/* dw[k,j] = sum_{n,p} dy[n,k,p] * x[n, (s_k + j) mod Cin, p] */
+int scc_oracle_backward_weight(const double *x, const double *dy, double *dw,
+                               int N, int Cin, int Cout, int HW, int cg, double co)
+{
+    int L, ov;
+    if (scc_oracle_window(Cin, cg, co, &L, &ov) != 0) return -1;
+    int *s = (int *)malloc(sizeof(int) * (size_t)Cout);
+    if (!s) return -2;
+    scc_oracle_starts(Cin, Cout, cg, co, s);
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int k = 0; k < Cout; ++k) {
+        for (int j = 0; j < L; ++j) {
+            int c = (s[k] + j) % Cin;
+            double acc = 0.0;
+            for (int n = 0; n < N; ++n) {
+                const double *go = dy + ((size_t)n * Cout + k) * HW;
+                const double *xi = x + ((size_t)n * Cin + c) * HW;
+                for (int p = 0; p < HW; ++p) acc += go[p] * xi[p];
+            }
+            dw[(size_t)k * L + j] = acc;
+        }
+    }
+    free(s);
+    return 0;
+}

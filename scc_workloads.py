@@ -1,0 +1,99 @@
+"""Seeded synthetic inputs for the SCC layer shapes that are measured and tested.
+
+This module holds layer shapes and random draws only: none of the method's
+arithmetic (no window index maths, no convolution).  It is the one module that
+both the CPU oracle's tests and the GPU path's tests/benchmark import, so that
+the two sides see identical arrays.
+
+The shapes stand in for image-classification layers (CIFAR-10 / ImageNet sized
+feature maps, Section 5.1 of the paper); the datasets themselves are not used.
+Draws: numpy PCG64 (``default_rng``), float64 normal draws cast to float32.
+Seed = 745000 + 100*config + 10*layer + {0: x, 1: w, 2: dy}.
+"""
+import math
+from dataclasses import dataclass, replace
+
+import numpy as np
+
+
+@dataclass(frozen=True)
+class Layer:
+    name: str
+    config: int           # index used in the seed
+    N: int
+    Cin: int
+    Cout: int
+    H: int
+    W: int
+    cg: int
+    co: float
+    x_law: str = "normal"      # "normal" -> N(0,1); "halfnormal" -> |N(0,1)| (post-ReLU)
+    w_std: float = 0.0         # 0 -> He: sqrt(2 / (Cin // cg))
+    layer: int = 0
+
+    @property
+    def L(self):
+        return self.Cin // self.cg
+
+    @property
+    def HW(self):
+        return self.H * self.W
+
+
+def seed_of(layer, which):
+    return 745000 + 100 * layer.config + 10 * layer.layer + {"x": 0, "w": 1, "dy": 2}[which]
+
+
+def make_inputs(layer, seed_offset=0):
+    """(x, w, dy) as float32 C-contiguous arrays for one layer."""
+    def draw(which, shape):
+        rng = np.random.default_rng(seed_of(layer, which) + 1000003 * seed_offset)
+        return rng.standard_normal(shape)
+
+    x = draw("x", (layer.N, layer.Cin, layer.H, layer.W))
+    if layer.x_law == "halfnormal":
+        x = np.abs(x)
+    std = layer.w_std if layer.w_std > 0 else math.sqrt(2.0 / layer.L)
+    w = draw("w", (layer.Cout, layer.L)) * std
+    dy = draw("dy", (layer.N, layer.Cout, layer.H, layer.W))
+    return (np.ascontiguousarray(x, dtype=np.float32),
+            np.ascontiguousarray(w, dtype=np.float32),
+            np.ascontiguousarray(dy, dtype=np.float32))
+
+
+# configs[0]: the small case the oracle finishes instantly.
+SMALL = Layer("c1_small", 1, N=1, Cin=32, Cout=32, H=8, W=8, cg=2, co=0.5, w_std=0.1)
+
+# configs[1]: the layer the headline metric is quoted on, and its overlap sweep.
+METRIC = Layer("c2_n128_c256_16x16_cg4_co50", 2, N=128, Cin=256, Cout=256, H=16, W=16, cg=4, co=0.5)
+METRIC_SWEEP = [replace(METRIC, name="c2_n128_c256_16x16_cg4_co%02d" % round(100 * co), co=co)
+                for co in (0.0, 0.25, 0.5, 0.75)]
+
+# configs[2]: late-stage 14x14 layer, post-ReLU activations (fp32 and bf16).
+LATE = Layer("c3_n64_c512_14x14_cg8_co50", 3, N=64, Cin=512, Cout=512, H=14, W=14, cg=8, co=0.5,
+             x_law="halfnormal")
+
+# configs[3]: channel-expanding layer whose windows wrap many times.
+EXPAND = Layer("c4_n128_c128to512_32x32_cg2_co33", 4, N=128, Cin=128, Cout=512, H=32, W=32, cg=2, co=0.33)
+
+# configs[4]: MobileNet-shaped stack (channels and spatial size after each
+# block's depthwise stage).  The configuration text spells out twelve channel
+# transitions and says thirteen blocks; the thirteenth is read as the final
+# 1024 -> 1024 block of the MobileNet shape.
+_STACK_SHAPES = [(32, 64, 32), (64, 128, 16), (128, 128, 16), (128, 256, 8), (256, 256, 8),
+                 (256, 512, 4), (512, 512, 4), (512, 512, 4), (512, 512, 4), (512, 512, 4),
+                 (512, 512, 4), (512, 1024, 2), (1024, 1024, 2)]
+STACK = [Layer("c5_l%02d_%dto%d_%dx%d" % (i, ci, co_, s, s), 5, N=128, Cin=ci, Cout=co_, H=s, W=s,
+               cg=2, co=0.5, layer=i) for i, (ci, co_, s) in enumerate(_STACK_SHAPES)]
+
+ALL_FULL = METRIC_SWEEP + [LATE, EXPAND] + STACK
+
+
+def algorithmic_bytes(layer, elem_bytes=4):
+    """Bytes one pass must move when every tensor crosses HBM exactly once."""
+    return elem_bytes * (layer.N * layer.HW * (layer.Cin + layer.Cout) + layer.Cout * layer.L)
+
+
+def algorithmic_flops(layer):
+    """2 * MACs of one pass: only the banded work, never the dense Cin*Cout product."""
+    return 2 * layer.N * layer.Cout * layer.L * layer.HW
