@@ -1,0 +1,116 @@
+/*
+ * scc.h - C ABI of the MI355X (gfx950) sliding-channel convolution library.
+ *
+ * Sliding-channel convolution (SCC) is the cross-channel step of a depthwise
+ * separable block in DSXplore (Section 3.1 of the paper): output channel
+ * ("filter") k is a weighted sum, at every pixel, over a window of
+ *     L = Cin / cg
+ * consecutive input channels.  Adjacent filters' windows overlap by
+ *     ov = int(co * L)                      (Algorithm 1: C truncation of the double product)
+ * channels, so the window of filter k starts at
+ *     s_k = (k * (L - ov)) mod Cin          (Algorithm 1 walked filter by filter; Algorithm 2)
+ * and wraps from channel Cin-1 to channel 0 (the "channel circle", Section 3.1).
+ * Weight j of filter k multiplies channel (s_k + j) mod Cin.
+ *
+ * Conventions shared by every entry point
+ *   - Every tensor pointer is a DEVICE pointer owned by the caller.  The library
+ *     allocates nothing, keeps no state between calls and never frees or
+ *     modifies an input.
+ *   - Tensors are dense, row-major:  x, dx : [N][Cin][H][W]
+ *                                    y, dy : [N][Cout][H][W]
+ *                                    w, dw : [Cout][L]
+ *     No spatial offset, padding or stride: output pixel (h, w) reads input
+ *     pixel (h, w) (Section 4.2, forward pass).  Only H*W matters.
+ *   - Outputs are overwritten, never accumulated into.  An output must not
+ *     alias an input.
+ *   - dtype SCC_F32: all tensors are IEEE binary32, arithmetic in binary32.
+ *     dtype SCC_BF16: x, w, y, dy, dx are bfloat16 (upper half of a binary32,
+ *     results rounded to nearest even), products accumulated in binary32;
+ *     dw is written as binary32 in BOTH dtypes.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Calls enqueue work and return; nothing synchronises the device.
+ *   - Return value: SCC_OK, or a negative scc_status.  Everything except
+ *     SCC_ERR_LAUNCH is decided on the host before any GPU call is made, so an
+ *     invalid call touches no memory.  Nothing is printed, nothing aborts.
+ *   - co is a double so that int(co * L) truncates exactly as Algorithm 1 does.
+ */
+#ifndef SCC_H
+#define SCC_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { SCC_F32 = 0, SCC_BF16 = 1 } scc_dtype;
+
+typedef enum {
+    SCC_OK = 0,
+    SCC_ERR_NULL = -1,      /* a required pointer is NULL */
+    SCC_ERR_SHAPE = -2,     /* a dimension <= 0, cg < 1, Cin % cg != 0, or a tensor too large to index */
+    SCC_ERR_OVERLAP = -3,   /* co is not finite or lies outside [0, 1] */
+    SCC_ERR_DTYPE = -4,     /* dtype is neither SCC_F32 nor SCC_BF16 */
+    SCC_ERR_WORKSPACE = -5, /* workspace missing, misaligned or smaller than the query says */
+    SCC_ERR_LAUNCH = -6     /* the HIP runtime refused a launch (hipGetLastError != hipSuccess) */
+} scc_status;
+
+/*
+ * Window arithmetic of Algorithm 1, host only (no GPU call).
+ *   L      <- Cin / cg
+ *   stride <- L - int(co * L)             distance between adjacent filters' window starts
+ *   period <- number of distinct windows among the Cout filters: the "cyclic
+ *             distance" of the channel-cyclic pattern (Section 4.2), i.e.
+ *             min(Cout, Cin / gcd(stride mod Cin, Cin)), and 1 when stride mod Cin == 0.
+ * Any output pointer may be NULL.  Errors: SCC_ERR_SHAPE, SCC_ERR_OVERLAP.
+ */
+int scc_window_params(int Cin, int Cout, int cg, double co, int* L, int* stride, int* period);
+
+/*
+ * Forward pass (Section 4.2, "Output-Centric Forward Pass"):
+ *     y[n,k,h,w] = sum_{j<L} w[k,j] * x[n, (s_k + j) mod Cin, h, w]
+ * x: in, N*Cin*H*W elements.  w: in, Cout*L elements.  y: out, N*Cout*H*W elements.
+ */
+int scc_forward(const void* x, const void* w, void* y,
+                int N, int Cin, int Cout, int H, int W, int cg, double co,
+                scc_dtype dtype, void* stream);
+
+/*
+ * Gradient with respect to the input (Section 4.2, "Input-Centric Backward Pass"):
+ * each input-gradient element gathers from the filters whose window covers its channel,
+ *     dx[n,c,h,w] = sum_{k : (c - s_k) mod Cin < L} w[k, (c - s_k) mod Cin] * dy[n,k,h,w]
+ * No atomics are used.  dy: in, N*Cout*H*W.  w: in, Cout*L.  dx: out, N*Cin*H*W.
+ * A channel no window covers (possible when Cout is small) receives zeros.
+ */
+int scc_backward_input(const void* dy, const void* w, void* dx,
+                       int N, int Cin, int Cout, int H, int W, int cg, double co,
+                       scc_dtype dtype, void* stream);
+
+/*
+ * Bytes of device scratch scc_backward_weight needs for this problem (may be 0).
+ * Returns 0 as well when the arguments are invalid; scc_backward_weight reports the error.
+ */
+size_t scc_backward_weight_workspace_bytes(int N, int Cin, int Cout, int H, int W, int cg, double co,
+                                           scc_dtype dtype);
+
+/*
+ * Gradient with respect to the weights (Section 4.2 names it among the trainable
+ * parameters' gradients; it is the derivative of the forward definition):
+ *     dw[k,j] = sum_{n,h,w} dy[n,k,h,w] * x[n, (s_k + j) mod Cin, h, w]
+ * x: in, N*Cin*H*W.  dy: in, N*Cout*H*W.  dw: out, Cout*L binary32 values (both dtypes).
+ * workspace: device scratch of at least scc_backward_weight_workspace_bytes(...) bytes,
+ * 256-byte aligned, owned by the caller, contents undefined before and after; may be NULL
+ * when the query returns 0.  The reduction order is fixed: two calls on the same inputs
+ * give bitwise identical results.
+ */
+int scc_backward_weight(const void* x, const void* dy, void* dw,
+                        int N, int Cin, int Cout, int H, int W, int cg, double co,
+                        scc_dtype dtype, void* workspace, size_t workspace_bytes, void* stream);
+
+/* Static, human-readable name of a status code (never NULL). */
+const char* scc_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SCC_H */

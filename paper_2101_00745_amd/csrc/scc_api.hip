@@ -1,0 +1,138 @@
+// C ABI of the SCC library: argument validation, window arithmetic, kernel selection.
+// Every check except the launch status happens on the host before any HIP call.
+#include "scc.h"
+#include "scc_common.h"
+
+#include <cmath>
+#include <limits>
+
+namespace {
+
+using scc::Problem;
+
+long long gcd_ll(long long a, long long b)
+{
+    while (b) {
+        long long t = a % b;
+        a = b;
+        b = t;
+    }
+    return a;
+}
+
+// Algorithm 1 in closed form.  Returns SCC_OK or the status that rejects the arguments.
+int make_problem(int N, int Cin, int Cout, int H, int W, int cg, double co, Problem* out)
+{
+    if (N <= 0 || Cin <= 0 || Cout <= 0 || H <= 0 || W <= 0 || cg < 1) return SCC_ERR_SHAPE;
+    if (Cin % cg != 0) return SCC_ERR_SHAPE;
+    if (!std::isfinite(co) || co < 0.0 || co > 1.0) return SCC_ERR_OVERLAP;
+    const long long HW = (long long)H * W;
+    const long long lim = std::numeric_limits<int>::max();
+    // the kernels index columns, planes of one sample and the weight matrix with 32-bit ints
+    if (HW > lim || HW * N > lim || HW * Cin > lim || HW * Cout > lim) return SCC_ERR_SHAPE;
+    const int L = Cin / cg;
+    if ((long long)Cout * L > lim) return SCC_ERR_SHAPE;
+    const int ov = (int)(co * (double)L);  // truncation of the double product, as Algorithm 1 writes it
+    const int stride = (L - ov) % Cin;     // L - ov == Cin only for cg == 1 with no overlap
+    Problem p;
+    p.N = N;
+    p.Cin = Cin;
+    p.Cout = Cout;
+    p.HW = (int)HW;
+    p.L = L;
+    p.stride = stride;
+    p.period = stride == 0 ? 1 : (int)(Cin / gcd_ll(stride, Cin));
+    p.NQ = HW * N;
+    *out = p;
+    return SCC_OK;
+}
+
+bool dtype_ok(scc_dtype d) { return d == SCC_F32 || d == SCC_BF16; }
+
+int launch_status(hipError_t e) { return e == hipSuccess ? SCC_OK : SCC_ERR_LAUNCH; }
+
+}  // namespace
+
+extern "C" {
+
+int scc_window_params(int Cin, int Cout, int cg, double co, int* L, int* stride, int* period)
+{
+    Problem p;
+    const int rc = make_problem(1, Cin, Cout, 1, 1, cg, co, &p);
+    if (rc != SCC_OK) return rc;
+    if (L) *L = p.L;
+    if (stride) *stride = p.L - (int)(co * (double)p.L);
+    if (period) *period = p.period < Cout ? p.period : Cout;
+    return SCC_OK;
+}
+
+int scc_forward(const void* x, const void* w, void* y, int N, int Cin, int Cout, int H, int W, int cg, double co,
+                scc_dtype dtype, void* stream)
+{
+    if (!x || !w || !y) return SCC_ERR_NULL;
+    Problem p;
+    const int rc = make_problem(N, Cin, Cout, H, W, cg, co, &p);
+    if (rc != SCC_OK) return rc;
+    if (!dtype_ok(dtype)) return SCC_ERR_DTYPE;
+    hipStream_t st = (hipStream_t)stream;
+    if (dtype == SCC_F32)
+        return launch_status(scc::launch_forward_generic((const float*)x, (const float*)w, (float*)y, p, st));
+    return launch_status(
+        scc::launch_forward_generic((const scc::bf16_t*)x, (const scc::bf16_t*)w, (scc::bf16_t*)y, p, st));
+}
+
+int scc_backward_input(const void* dy, const void* w, void* dx, int N, int Cin, int Cout, int H, int W, int cg,
+                       double co, scc_dtype dtype, void* stream)
+{
+    if (!dy || !w || !dx) return SCC_ERR_NULL;
+    Problem p;
+    const int rc = make_problem(N, Cin, Cout, H, W, cg, co, &p);
+    if (rc != SCC_OK) return rc;
+    if (!dtype_ok(dtype)) return SCC_ERR_DTYPE;
+    hipStream_t st = (hipStream_t)stream;
+    if (dtype == SCC_F32)
+        return launch_status(scc::launch_backward_input_generic((const float*)dy, (const float*)w, (float*)dx, p, st));
+    return launch_status(
+        scc::launch_backward_input_generic((const scc::bf16_t*)dy, (const scc::bf16_t*)w, (scc::bf16_t*)dx, p, st));
+}
+
+size_t scc_backward_weight_workspace_bytes(int N, int Cin, int Cout, int H, int W, int cg, double co, scc_dtype dtype)
+{
+    Problem p;
+    if (make_problem(N, Cin, Cout, H, W, cg, co, &p) != SCC_OK || !dtype_ok(dtype)) return 0;
+    return 0;
+}
+
+int scc_backward_weight(const void* x, const void* dy, void* dw, int N, int Cin, int Cout, int H, int W, int cg,
+                        double co, scc_dtype dtype, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!x || !dy || !dw) return SCC_ERR_NULL;
+    Problem p;
+    const int rc = make_problem(N, Cin, Cout, H, W, cg, co, &p);
+    if (rc != SCC_OK) return rc;
+    if (!dtype_ok(dtype)) return SCC_ERR_DTYPE;
+    const size_t need = scc_backward_weight_workspace_bytes(N, Cin, Cout, H, W, cg, co, dtype);
+    if (need > 0 && (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 255u) != 0))
+        return SCC_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    if (dtype == SCC_F32)
+        return launch_status(scc::launch_backward_weight_generic((const float*)x, (const float*)dy, (float*)dw, p, st));
+    return launch_status(
+        scc::launch_backward_weight_generic((const scc::bf16_t*)x, (const scc::bf16_t*)dy, (float*)dw, p, st));
+}
+
+const char* scc_status_string(int status)
+{
+    switch (status) {
+        case SCC_OK: return "SCC_OK";
+        case SCC_ERR_NULL: return "SCC_ERR_NULL: a required pointer is NULL";
+        case SCC_ERR_SHAPE: return "SCC_ERR_SHAPE: non-positive dimension, cg < 1, Cin not divisible by cg, or tensor too large";
+        case SCC_ERR_OVERLAP: return "SCC_ERR_OVERLAP: co must be finite and within [0, 1]";
+        case SCC_ERR_DTYPE: return "SCC_ERR_DTYPE: dtype must be SCC_F32 or SCC_BF16";
+        case SCC_ERR_WORKSPACE: return "SCC_ERR_WORKSPACE: workspace missing, misaligned or too small";
+        case SCC_ERR_LAUNCH: return "SCC_ERR_LAUNCH: the HIP runtime refused the kernel launch";
+        default: return "unknown scc status";
+    }
+}
+
+}  // extern "C"

@@ -1,0 +1,121 @@
+"""Host-side tests of the C ABI: the library loads, exports what include/scc.h declares,
+and rejects bad arguments on the host (no GPU is touched by any call made here)."""
+import ctypes
+import math
+import os
+import re
+
+import pytest
+
+import paper_2101_00745_amd as S
+from paper_2101_00745_amd import scc as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = ctypes.c_void_p(0x1000)  # non-NULL, never dereferenced: every call below fails validation first
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "scc.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(scc_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = S.load()
+    names = declared_functions()
+    assert sorted(names) == sorted(B.SYMBOLS)
+    for name in names:
+        assert getattr(lib, name) is not None
+
+
+def test_status_strings():
+    for code in range(0, -7, -1):
+        s = S.scc_status_string(code)
+        assert s.startswith("SCC_")
+    assert "unknown" in S.scc_status_string(-99)
+
+
+def alg1_period(Cin, Cout, cg, co):
+    gw = Cin // cg
+    seen, sv, ev = [], 0, gw
+    for _ in range(Cout):
+        st = sv % Cin
+        if st in seen:
+            break
+        seen.append(st)
+        sv = ev - int(co * gw)
+        ev = sv + gw
+    return len(seen)
+
+
+@pytest.mark.parametrize("Cin,Cout,cg,co", [(4, 4, 2, 0.5), (256, 256, 4, 0.0), (256, 256, 4, 0.25), (256, 256, 4, 0.5),
+                                            (256, 256, 4, 0.75), (512, 512, 8, 0.5), (128, 512, 2, 0.33),
+                                            (6, 9, 2, 1 / 3), (16, 5, 1, 0.0), (16, 5, 1, 1.0), (16, 3, 2, 0.25),
+                                            (100, 77, 1, 0.29), (1024, 1024, 2, 0.5)])
+def test_window_params(Cin, Cout, cg, co):
+    L, stride, period = S.scc_window_params(Cin, Cout, cg, co)
+    assert L == Cin // cg
+    assert stride == L - int(co * L)
+    assert period == alg1_period(Cin, Cout, cg, co)
+
+
+def test_window_params_paper_values():
+    # Section 5.4: Cin=4, co=50% (cg=2) -> cyclic distance 4; Section 4.2: cg=2/co=50% -> 4 for any Cin
+    assert S.scc_window_params(4, 8, 2, 0.5)[2] == 4
+    assert S.scc_window_params(512, 512, 2, 0.5)[2] == 4
+    assert S.scc_window_params(64, 128, 2, 0.5)[0] == 32
+
+
+BAD = [
+    (dict(N=0), B.SccError, -2), (dict(Cin=-4), B.SccError, -2), (dict(Cout=0), B.SccError, -2),
+    (dict(H=0), B.SccError, -2), (dict(W=-1), B.SccError, -2), (dict(cg=0), B.SccError, -2),
+    (dict(cg=3), B.SccError, -2),                      # 8 % 3 != 0
+    (dict(co=-0.01), B.SccError, -3), (dict(co=1.01), B.SccError, -3), (dict(co=math.nan), B.SccError, -3),
+    (dict(co=math.inf), B.SccError, -3), (dict(dtype=2), B.SccError, -4), (dict(dtype=-1), B.SccError, -4),
+    (dict(N=1 << 20, H=1 << 10, W=1 << 10), B.SccError, -2),   # N*H*W overflows 32-bit columns
+]
+
+
+def _call(which, **over):
+    a = dict(N=2, Cin=8, Cout=6, H=3, W=3, cg=2, co=0.5, dtype=0)
+    a.update(over)
+    lib = S.load()
+    shape = (a["N"], a["Cin"], a["Cout"], a["H"], a["W"], a["cg"], a["co"], a["dtype"])
+    if which == "fwd":
+        return lib.scc_forward(FAKE, FAKE, FAKE, *shape, None)
+    if which == "bwi":
+        return lib.scc_backward_input(FAKE, FAKE, FAKE, *shape, None)
+    return lib.scc_backward_weight(FAKE, FAKE, FAKE, *shape, None, 0, None)
+
+
+@pytest.mark.parametrize("which", ["fwd", "bwi", "bww"])
+@pytest.mark.parametrize("over,exc,code", BAD)
+def test_invalid_arguments_are_rejected_on_the_host(which, over, exc, code):
+    assert _call(which, **over) == code
+    shape = dict(N=2, Cin=8, Cout=6, H=3, W=3, cg=2, co=0.5, dtype=0)
+    shape.update(over)
+    assert S.load().scc_backward_weight_workspace_bytes(*[shape[k] for k in
+                                                         ("N", "Cin", "Cout", "H", "W", "cg", "co", "dtype")]) == 0
+
+
+def test_null_pointers_are_rejected():
+    lib = S.load()
+    shape = (2, 8, 6, 3, 3, 2, 0.5, 0)
+    for i in range(3):
+        ptrs = [FAKE, FAKE, FAKE]
+        ptrs[i] = None
+        assert lib.scc_forward(*ptrs, *shape, None) == -1
+        assert lib.scc_backward_input(*ptrs, *shape, None) == -1
+        assert lib.scc_backward_weight(*ptrs, *shape, None, 0, None) == -1
+
+
+def test_binding_refuses_cpu_tensors():
+    import torch
+    x = torch.zeros(1, 4, 2, 2)
+    w = torch.zeros(4, 2)
+    with pytest.raises(ValueError):
+        S.scc_forward(x, w, 2, 0.5)
+    with pytest.raises(ValueError):
+        S.scc_backward_input(x, w, 4, 2, 0.5)
+    with pytest.raises(ValueError):
+        S.scc_backward_weight(x, x, 2, 0.5)

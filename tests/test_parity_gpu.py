@@ -1,0 +1,200 @@
+"""GPU parity: the HIP library (through its C ABI binding) against the fp64 CPU oracle,
+element by element on identical seeded inputs.
+
+Bar (written here, from the benchmark spec): max|gpu - ref| / max|ref| <= 2e-5 for
+fp32 tensors and <= 1e-2 for bf16 tensors.  bf16 inputs are rounded to bf16 once, on the
+host, and both sides consume those rounded values.
+"""
+import dataclasses
+
+import numpy as np
+import pytest
+import torch
+
+import scc_workloads as Wk
+from oracle import scc_oracle as O
+
+pytestmark = pytest.mark.gpu
+
+TOL = {torch.float32: 2e-5, torch.bfloat16: 1e-2}
+
+
+@pytest.fixture(scope="module")
+def S():
+    import paper_2101_00745_amd as lib
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    lib.load()  # raises if libscc_hip.so is not built: no fallback
+    return lib
+
+
+def rel_err(got, ref):
+    got = np.asarray(got, dtype=np.float64)
+    denom = float(np.max(np.abs(ref)))
+    if denom == 0.0:
+        return float(np.max(np.abs(got)))
+    return float(np.max(np.abs(got - ref))) / denom
+
+
+def to_dev(a, dtype):
+    return torch.from_numpy(a).to(dtype).cuda()
+
+
+def host(t):
+    return t.float().cpu().numpy()
+
+
+def check_layer(S, layer, dtype=torch.float32, seed_offset=0, passes=("fwd", "bwi", "bww")):
+    x, w, dy = Wk.make_inputs(layer, seed_offset)
+    xd, wd, dyd = to_dev(x, dtype), to_dev(w, dtype), to_dev(dy, dtype)
+    xr, wr, dyr = host(xd), host(wd), host(dyd)          # exactly the values the GPU sees
+    tol = TOL[dtype]
+    errs = {}
+    if "fwd" in passes:
+        y = S.scc_forward(xd, wd, layer.cg, layer.co)
+        assert y.shape == (layer.N, layer.Cout, layer.H, layer.W) and y.dtype == dtype
+        errs["fwd"] = rel_err(host(y), O.forward(xr, wr, layer.cg, layer.co))
+    if "bwi" in passes:
+        dx = S.scc_backward_input(dyd, wd, layer.Cin, layer.cg, layer.co)
+        assert dx.shape == x.shape and dx.dtype == dtype
+        errs["bwi"] = rel_err(host(dx), O.backward_input(dyr, wr, layer.Cin, layer.cg, layer.co))
+    if "bww" in passes:
+        dw = S.scc_backward_weight(xd, dyd, layer.cg, layer.co)
+        assert dw.shape == (layer.Cout, layer.L) and dw.dtype == torch.float32
+        # dw is float32 in both dtypes; for bf16 the inputs are bf16-rounded and the bar is the bf16 one
+        errs["bww"] = rel_err(host(dw), O.backward_weight(xr, dyr, layer.cg, layer.co))
+    torch.cuda.synchronize()
+    for k, e in errs.items():
+        assert e <= tol, "%s %s %s: rel err %.3e > %.1e" % (layer.name, dtype, k, e, tol)
+    return errs
+
+
+def small(name, N, Cin, Cout, H, W, cg, co, **kw):
+    return Wk.Layer(name, 9, N=N, Cin=Cin, Cout=Cout, H=H, W=W, cg=cg, co=co, **kw)
+
+
+# Shapes the oracle finishes at once, spanning several tiles with ragged tails: odd H*W,
+# H*W below one wavefront, Cout not a multiple of the period, Cout below the period, wraps.
+SMALL_SHAPES = [
+    Wk.SMALL,
+    small("tiny_paper_example", 1, 4, 4, 1, 1, 2, 0.5),
+    small("one_pixel", 3, 8, 8, 1, 1, 2, 0.5),
+    small("odd_hw", 2, 24, 40, 7, 5, 3, 0.5),
+    small("hw_3x3_many_n", 37, 16, 20, 3, 3, 2, 0.25),
+    small("cout_below_period", 2, 64, 5, 6, 6, 4, 0.75),
+    small("cout_not_multiple_of_period", 2, 64, 77, 9, 9, 4, 0.5),
+    small("one_group_rotated", 2, 48, 40, 5, 5, 1, 0.3),
+    small("one_group_no_overlap", 2, 32, 16, 4, 4, 1, 0.0),
+    small("full_overlap", 2, 32, 48, 4, 4, 2, 1.0),
+    small("zero_overlap_groups", 3, 96, 96, 10, 10, 4, 0.0),
+    small("coprime_stride_wraps", 2, 128, 200, 8, 8, 2, 0.33),
+    small("ragged_columns", 5, 64, 64, 13, 11, 2, 0.5),
+    small("expand", 2, 32, 256, 12, 12, 2, 0.5),
+    small("shrink", 2, 256, 32, 12, 12, 4, 0.5),
+    small("l_is_one", 2, 16, 16, 5, 5, 16, 0.5),
+    small("wide_window_1024", 1, 1024, 96, 2, 2, 2, 0.5),
+    small("mid_256_16x16", 4, 256, 256, 16, 16, 4, 0.5),
+    small("mid_512_14x14", 3, 512, 512, 14, 14, 8, 0.5, x_law="halfnormal"),
+]
+
+
+@pytest.mark.parametrize("layer", SMALL_SHAPES, ids=lambda l: l.name)
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])
+def test_small_shapes(S, layer, dtype):
+    check_layer(S, layer, dtype)
+
+
+def test_random_small_sweep(S):
+    rng = np.random.default_rng(20210100745)
+    for i in range(40):
+        cg = int(rng.choice([1, 2, 3, 4, 8]))
+        Cin = cg * int(rng.integers(1, 24))
+        Cout = int(rng.integers(1, 80))
+        H, W = int(rng.integers(1, 12)), int(rng.integers(1, 12))
+        N = int(rng.integers(1, 6))
+        co = float(rng.choice([0.0, 0.1, 0.25, 1 / 3, 0.33, 0.5, 0.66, 0.75, 1.0, rng.random()]))
+        layer = small("rand%d" % i, N, Cin, Cout, H, W, cg, co)
+        check_layer(S, layer, torch.float32, seed_offset=i)
+
+
+# Full-size configurations, in the launch configuration the benchmark times.
+@pytest.mark.parametrize("layer", Wk.METRIC_SWEEP, ids=lambda l: l.name)
+def test_metric_layer_overlap_sweep(S, layer):
+    check_layer(S, layer, torch.float32)
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])
+def test_late_stage_layer(S, dtype):
+    check_layer(S, Wk.LATE, dtype)
+
+
+def test_metric_layer_bf16(S):
+    check_layer(S, Wk.METRIC, torch.bfloat16)
+
+
+def test_channel_expanding_layer(S):
+    check_layer(S, Wk.EXPAND, torch.float32)
+
+
+@pytest.mark.parametrize("layer", Wk.STACK, ids=lambda l: l.name)
+def test_mobilenet_shaped_stack(S, layer):
+    check_layer(S, layer, torch.float32)
+
+
+def test_adjoint_identity_on_gpu_outputs(S):
+    layer = Wk.METRIC
+    x, w, dy = Wk.make_inputs(layer)
+    xd, wd, dyd = to_dev(x, torch.float32), to_dev(w, torch.float32), to_dev(dy, torch.float32)
+    y = host(S.scc_forward(xd, wd, layer.cg, layer.co)).astype(np.float64)
+    dx = host(S.scc_backward_input(dyd, wd, layer.Cin, layer.cg, layer.co)).astype(np.float64)
+    dw = host(S.scc_backward_weight(xd, dyd, layer.cg, layer.co)).astype(np.float64)
+    a, b, c = float(np.sum(dy * y)), float(np.sum(dx * x)), float(np.sum(dw * w))
+    scale = float(np.sqrt(np.sum((dy * y) ** 2)))      # size of the terms being summed
+    assert abs(a - b) <= 1e-3 * scale and abs(a - c) <= 1e-3 * scale
+
+
+def test_two_runs_are_bitwise_equal(S):
+    for layer in (Wk.METRIC, small("ragged_columns", 5, 64, 64, 13, 11, 2, 0.5)):
+        x, w, dy = Wk.make_inputs(layer)
+        xd, wd, dyd = to_dev(x, torch.float32), to_dev(w, torch.float32), to_dev(dy, torch.float32)
+        runs = []
+        for _ in range(2):
+            runs.append((S.scc_forward(xd, wd, layer.cg, layer.co).clone(),
+                         S.scc_backward_input(dyd, wd, layer.Cin, layer.cg, layer.co).clone(),
+                         S.scc_backward_weight(xd, dyd, layer.cg, layer.co).clone()))
+        for a, b in zip(*runs):
+            assert torch.equal(a, b)
+
+
+def test_outputs_are_overwritten_not_accumulated(S):
+    layer = Wk.SMALL
+    x, w, dy = Wk.make_inputs(layer)
+    xd, wd, dyd = to_dev(x, torch.float32), to_dev(w, torch.float32), to_dev(dy, torch.float32)
+    y0 = S.scc_forward(xd, wd, layer.cg, layer.co)
+    junk = torch.full_like(y0, 1e30)
+    assert torch.equal(S.scc_forward(xd, wd, layer.cg, layer.co, out=junk), y0)
+    dx0 = S.scc_backward_input(dyd, wd, layer.Cin, layer.cg, layer.co)
+    junk = torch.full_like(dx0, float("nan"))
+    assert torch.equal(S.scc_backward_input(dyd, wd, layer.Cin, layer.cg, layer.co, out=junk), dx0)
+    dw0 = S.scc_backward_weight(xd, dyd, layer.cg, layer.co)
+    junk = torch.full_like(dw0, float("nan"))
+    assert torch.equal(S.scc_backward_weight(xd, dyd, layer.cg, layer.co, out=junk), dw0)
+
+
+def test_uncovered_channels_get_zero_gradient(S):
+    # Cout below the period: some input channels lie in no window
+    layer = small("uncovered", 2, 64, 2, 4, 4, 4, 0.0)
+    x, w, dy = Wk.make_inputs(layer)
+    dx = host(S.scc_backward_input(to_dev(dy, torch.float32), to_dev(w, torch.float32), 64, 4, 0.0))
+    assert np.all(dx[:, 32:] == 0.0) and np.any(dx[:, :32] != 0.0)
+
+
+def test_non_default_stream(S):
+    layer = dataclasses.replace(Wk.SMALL, N=4)
+    x, w, dy = Wk.make_inputs(layer)
+    xd, wd = to_dev(x, torch.float32), to_dev(w, torch.float32)
+    torch.cuda.synchronize()
+    st = torch.cuda.Stream()
+    with torch.cuda.stream(st):
+        y = S.scc_forward(xd, wd, layer.cg, layer.co)
+    st.synchronize()
+    assert rel_err(host(y), O.forward(x, w, layer.cg, layer.co)) <= 2e-5
