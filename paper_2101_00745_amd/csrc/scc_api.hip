@@ -75,8 +75,11 @@ int scc_forward(const void* x, const void* w, void* y, int N, int Cin, int Cout,
     if (rc != SCC_OK) return rc;
     if (!dtype_ok(dtype)) return SCC_ERR_DTYPE;
     hipStream_t st = (hipStream_t)stream;
-    if (dtype == SCC_F32)
+    if (dtype == SCC_F32) {
+        if (scc::forward_mfma_eligible(p))
+            return launch_status(scc::launch_forward_mfma((const float*)x, (const float*)w, (float*)y, p, st));
         return launch_status(scc::launch_forward_generic((const float*)x, (const float*)w, (float*)y, p, st));
+    }
     return launch_status(
         scc::launch_forward_generic((const scc::bf16_t*)x, (const scc::bf16_t*)w, (scc::bf16_t*)y, p, st));
 }

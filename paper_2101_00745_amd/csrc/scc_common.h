@@ -37,4 +37,8 @@ template <typename T> hipError_t launch_forward_generic(const T* x, const T* w, 
 template <typename T> hipError_t launch_backward_input_generic(const T* dy, const T* w, T* dx, const Problem& p, hipStream_t st);
 template <typename T> hipError_t launch_backward_weight_generic(const T* x, const T* dy, float* dw, const Problem& p, hipStream_t st);
 
+// Matrix-core (fp32 MFMA) kernels: scc_mfma_*.hip
+bool forward_mfma_eligible(const Problem& p);
+hipError_t launch_forward_mfma(const float* x, const float* w, float* y, const Problem& p, hipStream_t st);
+
 }  // namespace scc
