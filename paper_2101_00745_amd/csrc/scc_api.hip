@@ -93,8 +93,11 @@ int scc_backward_input(const void* dy, const void* w, void* dx, int N, int Cin, 
     if (rc != SCC_OK) return rc;
     if (!dtype_ok(dtype)) return SCC_ERR_DTYPE;
     hipStream_t st = (hipStream_t)stream;
-    if (dtype == SCC_F32)
+    if (dtype == SCC_F32) {
+        if (scc::backward_input_mfma_eligible(p))
+            return launch_status(scc::launch_backward_input_mfma((const float*)dy, (const float*)w, (float*)dx, p, st));
         return launch_status(scc::launch_backward_input_generic((const float*)dy, (const float*)w, (float*)dx, p, st));
+    }
     return launch_status(
         scc::launch_backward_input_generic((const scc::bf16_t*)dy, (const scc::bf16_t*)w, (scc::bf16_t*)dx, p, st));
 }

@@ -40,5 +40,7 @@ template <typename T> hipError_t launch_backward_weight_generic(const T* x, cons
 // Matrix-core (fp32 MFMA) kernels: scc_mfma_*.hip
 bool forward_mfma_eligible(const Problem& p);
 hipError_t launch_forward_mfma(const float* x, const float* w, float* y, const Problem& p, hipStream_t st);
+bool backward_input_mfma_eligible(const Problem& p);
+hipError_t launch_backward_input_mfma(const float* dy, const float* w, float* dx, const Problem& p, hipStream_t st);
 
 }  // namespace scc

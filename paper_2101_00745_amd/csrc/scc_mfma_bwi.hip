@@ -1,0 +1,198 @@
+// Grad-input of SCC on the gfx950 matrix cores (fp32 MFMA), as a per-input-channel gather.
+//
+// dx[n,c,p] = sum over filters k whose window covers c of w[k,(c-s_k) mod Cin] * dy[n,k,p]
+// (Section 4.2, input-centric backward: every input-gradient element PULLS from the filters
+// covering its channel, so nothing is accumulated with atomics).
+//
+// A tile is 32 consecutive input channels c0..c0+31 times 32*CT columns.  The filters that can
+// cover any of those channels are the ones whose window start s lies in (c0-L, c0+31] on the
+// channel circle; starts are the multiples g*m (see scc_band.h), so the contraction runs over
+// the grid (mm, i): window m = mlo+mm, i-th filter of that window, k = r(m) + P*i.  The A
+// operand of a K-slot is row k of the weight matrix read at consecutive positions by
+// consecutive channels (one coalesced 128-byte read per half-wave), zero where the window
+// does not reach the channel; the B operand is the plane dy[n,k,:].
+#include "scc_band.h"
+#include "scc_common.h"
+
+namespace scc {
+
+namespace {
+
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+struct BwiTiling {
+    Band b;
+    int CB;   // channel blocks of 32
+    int NCT;  // column tiles, padded to a multiple of 8
+    int FG;   // workgroups per column tile = ceil(CB / 4)
+};
+
+__device__ __forceinline__ int floor_div(int a, int b)  // b > 0
+{
+    const int q = a / b;
+    return (a % b != 0 && a < 0) ? q - 1 : q;
+}
+
+template <int CT, int KC, bool VEC>
+__global__ __launch_bounds__(256) void backward_input_mfma32(const float* __restrict__ dy, const float* __restrict__ w,
+                                                             float* __restrict__ dx, Problem P, BwiTiling T)
+{
+    typedef float bvec __attribute__((ext_vector_type(CT)));
+    const int bid = blockIdx.x;
+    const int xcd = bid & 7, slot = bid >> 3;
+    const int ct = (slot / T.FG) * 8 + xcd;
+    const int fg = slot % T.FG;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int cb = fg * 4 + wave;
+    if (cb >= T.CB || (long long)ct * (32 * CT) >= P.NQ) return;
+
+    const int lane = threadIdx.x & 63;
+    const int f = lane & 31, h = lane >> 5;
+    const int c0 = cb * 32;
+    const int c = c0 + f;                       // this lane's input channel (A row)
+    const bool cvalid = c < P.Cin;
+    // unwrapped window index range: g*m in [c0-L+1, c0+31]
+    const int mlo = -floor_div(P.L - 1 - c0, T.b.g);   // ceil((c0-L+1)/g)
+    const int M = floor_div(c0 + 31, T.b.g) - mlo + 1;  // window starts this block can see (>= 1)
+    // K-steps: each half-wave walks Uh (window, filter) slots; an even number of chunks
+    const int Uh = ((M * T.b.F + 1) / 2 + 2 * KC - 1) / (2 * KC) * (2 * KC);
+    const char* wb = (const char*)w;
+    const char* gb = (const char*)dy;
+
+    uint32_t gcol[CT], dcol[CT];
+    bool live[CT];
+#pragma unroll
+    for (int cc = 0; cc < CT; ++cc) {
+        const uint32_t q = (uint32_t)ct * (32 * CT) + (VEC ? f * CT + cc : cc * 32 + f);
+        live[cc] = q < (uint32_t)P.NQ;
+        const uint32_t qq = live[cc] ? q : 0u;
+        const uint32_t n = qq / (uint32_t)P.HW, p = qq % (uint32_t)P.HW;
+        gcol[cc] = (n * (uint32_t)P.Cout * (uint32_t)P.HW + p) * 4u;
+        dcol[cc] = n * (uint32_t)P.Cin * (uint32_t)P.HW + p;
+    }
+
+    // K-slot state of this half-wave: slot u = h*Uh + t  <->  (mm, i) = (u / F, u % F)
+    const int u0 = h * Uh;
+    int mm = u0 / T.b.F, i = u0 % T.b.F;
+    int mw = (mlo + mm) % T.b.P;                 // window index on the circle
+    if (mw < 0) mw += T.b.P;
+    int r = (int)(((uint32_t)mw * (uint32_t)T.b.inv) % (uint32_t)T.b.P);   // residue class owning window mw
+    int ju = c - T.b.g * (mlo + mm);             // position of channel c inside that window (unwrapped)
+    const uint32_t plane = (uint32_t)P.HW * 4u;
+
+    f32x16 acc[CT];
+#pragma unroll
+    for (int cc = 0; cc < CT; ++cc)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[cc][v] = 0.f;
+
+    auto load_chunk = [&](float (&ad)[KC], uint32_t& am, bvec (&bd)[KC]) {
+        am = 0;
+#pragma unroll
+        for (int s = 0; s < KC; ++s) {
+            const int k = r + T.b.P * i;
+            const bool kvalid = (mm < M) && (k < P.Cout);
+            const bool in = kvalid && cvalid && ju >= 0 && ju < P.L;
+            ad[s] = *(const float*)(wb + (uint32_t)(in ? (k * P.L + ju) * 4 : 0));
+            am |= in ? (1u << s) : 0u;
+            const uint32_t rowofs = (uint32_t)(kvalid ? k : 0) * plane;
+            if (VEC) {
+                bd[s] = *(const bvec*)(gb + (uint32_t)(gcol[0] + rowofs));
+            } else {
+#pragma unroll
+                for (int cc = 0; cc < CT; ++cc) bd[s][cc] = *(const float*)(gb + (uint32_t)(gcol[cc] + rowofs));
+            }
+            // next slot: next filter of this window, or the first filter of the next window
+            ++i;
+            const bool nextw = (i == T.b.F);
+            i = nextw ? 0 : i;
+            mm += nextw ? 1 : 0;
+            ju -= nextw ? T.b.g : 0;
+            int rn = r + T.b.inv;                // r(m+1) = r(m) + inv (mod P)
+            rn = (rn >= T.b.P) ? rn - T.b.P : rn;
+            r = nextw ? rn : r;
+        }
+    };
+    auto mma_chunk = [&](const float (&as)[KC], uint32_t am, const bvec (&bs)[KC]) {
+#pragma unroll
+        for (int s = 0; s < KC; ++s) {
+            const float av = (am >> s) & 1u ? as[s] : 0.f;
+#pragma unroll
+            for (int cc = 0; cc < CT; ++cc)
+                acc[cc] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bs[s][cc], acc[cc], 0, 0, 0);
+        }
+    };
+
+    // software pipelined over an even number of chunks (Uh is a multiple of 2*KC)
+    float a0[KC], a1[KC];
+    bvec b0[KC], b1[KC];
+    uint32_t m0, m1;
+    const int nch = Uh / KC;
+    load_chunk(a0, m0, b0);
+    for (int cix = 0; cix + 2 < nch; cix += 2) {
+        load_chunk(a1, m1, b1);
+        mma_chunk(a0, m0, b0);
+        load_chunk(a0, m0, b0);
+        mma_chunk(a1, m1, b1);
+    }
+    load_chunk(a1, m1, b1);
+    mma_chunk(a0, m0, b0);
+    mma_chunk(a1, m1, b1);
+
+    // accumulator register v holds tile row 8*(v/4) + 4*h + v%4 (= channel c0 + that), column f
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+        const int cr = c0 + 8 * (v >> 2) + 4 * h + (v & 3);
+        if (cr < P.Cin) {
+            if (VEC) {
+                if (live[0]) {
+                    bvec o;
+#pragma unroll
+                    for (int cc = 0; cc < CT; ++cc) o[cc] = acc[cc][v];
+                    *(bvec*)(dx + (size_t)dcol[0] + (size_t)cr * P.HW) = o;
+                }
+            } else {
+#pragma unroll
+                for (int cc = 0; cc < CT; ++cc)
+                    if (live[cc]) dx[(size_t)dcol[cc] + (size_t)cr * P.HW] = acc[cc][v];
+            }
+        }
+    }
+}
+
+template <int CT, bool VEC>
+void launch_cfg(const float* dy, const float* w, float* dx, const Problem& p, hipStream_t st)
+{
+    constexpr int KC = 8;
+    BwiTiling t;
+    t.b = make_band(p);
+    t.CB = (p.Cin + 31) / 32;
+    const long long nct = (p.NQ + 32 * CT - 1) / (32 * CT);
+    t.NCT = (int)((nct + 7) / 8 * 8);
+    t.FG = (t.CB + 3) / 4;
+    const long long blocks = (long long)t.NCT * t.FG;
+    backward_input_mfma32<CT, KC, VEC><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(dy, w, dx, p, t);
+}
+
+}  // namespace
+
+bool backward_input_mfma_eligible(const Problem& p)
+{
+    const long long rows = p.Cin > p.Cout ? p.Cin : p.Cout;
+    // (window, filter) slots of one block, (L+30)/g + 1 windows at most, must fit an int
+    const Band b = make_band(p);
+    if (((long long)(p.L + 30) / b.g + 1) * b.F > (1 << 28)) return false;
+    return p.L >= 8 && p.NQ >= 64 && p.Cin >= 8 && p.Cin < 65536 && (long long)p.NQ * rows * 4 < (1ll << 32) &&
+           (long long)p.Cout * p.L * 4 < (1ll << 31);
+}
+
+hipError_t launch_backward_input_mfma(const float* dy, const float* w, float* dx, const Problem& p, hipStream_t st)
+{
+    if (p.HW % 4 == 0 && (((uintptr_t)dy | (uintptr_t)dx) & 15u) == 0)
+        launch_cfg<4, true>(dy, w, dx, p, st);
+    else
+        launch_cfg<2, false>(dy, w, dx, p, st);
+    return hipGetLastError();
+}
+
+}  // namespace scc

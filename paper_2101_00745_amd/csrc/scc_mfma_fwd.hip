@@ -25,15 +25,23 @@ struct FwdTiling {
     Band b;
     int TI, TM;    // tile = TM starts x TI filters per start; TI*TM <= 32 (TM is capped by P)
     int IB, MB;    // tiles along i and m
-    int Uh;        // K-steps per tile (multiple of 4); each half-wave covers Uh channels
+    int Uh;        // K-steps per tile (multiple of the chunk length); each half-wave covers Uh channels
     int NCT;       // column tiles (of 32*CT columns), padded to a multiple of 8
     int FG;        // workgroups per column tile = ceil(IB*MB / 4)
 };
 
-template <int CT>
+// CT   column groups of 32 per wavefront (the tile is 32 filters x 32*CT columns)
+// KC   K-steps per pipelined chunk of B loads
+// AL4  g and L are multiples of 4: groups of four weights are wholly inside or outside a window
+// VEC  H*W is a multiple of CT: a lane owns CT CONSECUTIVE columns (one CT*4-byte load per plane,
+//      one CT*4-byte store per output row); otherwise a lane owns columns f, f+32, ...
+template <int CT, int KC, bool AL4, bool VEC>
 __global__ __launch_bounds__(256) void forward_mfma32(const float* __restrict__ x, const float* __restrict__ w,
                                                       float* __restrict__ y, Problem P, FwdTiling T)
 {
+    typedef float bvec __attribute__((ext_vector_type(CT)));
+    constexpr int KA = 32;  // K-steps per chunk of A loads: 32 consecutive weights = one 128-byte line per lane
+
     // workgroup -> (column tile, filter-tile group); all groups of a column tile share blockIdx % 8,
     // i.e. one XCD and its L2, because they re-read the same channel planes.
     const int bid = blockIdx.x;
@@ -51,27 +59,30 @@ __global__ __launch_bounds__(256) void forward_mfma32(const float* __restrict__ 
     // ---- A side: this lane's filter -------------------------------------------------------
     const int mi = f / T.TI, ii = f % T.TI;
     const int m = mb * T.TM + mi, i = ib * T.TI + ii;
-    const int k = (int)(((long long)m * T.b.inv) % T.b.P) + T.b.P * i;
+    const int k = (int)(((uint32_t)m * (uint32_t)T.b.inv) % (uint32_t)T.b.P) + T.b.P * i;  // P < 65536
     const bool fvalid = (mi < T.TM) && (m < T.b.P) && (k < P.Cout);
     const int off = T.b.g * mi;                      // this filter's window starts `off` channels into the span
-    const float* wk = w + (long long)(fvalid ? k : 0) * P.L;
+    const int wrow = (fvalid ? k : 0) * P.L;         // first weight of this lane's filter
     const int lo = T.b.g * mb * T.TM;                // first channel of the span (< Cin)
+    const char* wb = (const char*)w;
+    const char* xb = (const char*)x;
 
-    // ---- B side: this lane's columns ---------------------------------------------------------
-    const float* xcol[CT];
+    // ---- B side: this lane's columns (byte offsets from x; the launcher checked they fit 32 bits) ----
+    uint32_t xcol[CT], ycol[CT];
     bool live[CT];
-    long long ycol[CT];
 #pragma unroll
     for (int c = 0; c < CT; ++c) {
-        const long long q = ((long long)ct * CT + c) * 32 + f;
-        live[c] = q < P.NQ;
-        const long long qq = live[c] ? q : 0;
-        const int n = (int)(qq / P.HW), p = (int)(qq % P.HW);
-        xcol[c] = x + (long long)n * P.Cin * P.HW + p;
-        ycol[c] = (long long)n * P.Cout * P.HW + p;
+        const uint32_t q = (uint32_t)ct * (32 * CT) + (VEC ? f * CT + c : c * 32 + f);
+        live[c] = q < (uint32_t)P.NQ;
+        const uint32_t qq = live[c] ? q : 0u;
+        const uint32_t n = qq / (uint32_t)P.HW, p = qq % (uint32_t)P.HW;
+        xcol[c] = (n * (uint32_t)P.Cin * (uint32_t)P.HW + p) * 4u;
+        ycol[c] = n * (uint32_t)P.Cout * (uint32_t)P.HW + p;
     }
-    int ch = (lo + h * T.Uh) % P.Cin;                // channel this half-wave reads at step 0
-    int jj = h * T.Uh - off;                         // weight index of this lane at step 0
+    const uint32_t plane = (uint32_t)P.HW * 4u;                  // bytes between channel planes
+    const uint32_t wrap = (uint32_t)P.Cin * plane;               // bytes of one sample's channels
+    uint32_t rowofs = (uint32_t)((lo + h * T.Uh) % P.Cin) * plane;  // plane this half-wave reads next
+    int jj = h * T.Uh - off;                                     // weight index this lane reads next
 
     f32x16 acc[CT];
 #pragma unroll
@@ -79,44 +90,90 @@ __global__ __launch_bounds__(256) void forward_mfma32(const float* __restrict__ 
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[c][v] = 0.f;
 
-    for (int t = 0; t < T.Uh; t += 4) {
-        float a[4];
-        if (fvalid && jj >= 0 && jj + 3 < P.L) {
-            const f32x4u a4 = *(const f32x4u*)(wk + jj);
-            a[0] = a4[0]; a[1] = a4[1]; a[2] = a4[2]; a[3] = a4[3];
-        } else {
+    // A operands of KA K-steps.  Loads are branch free: a lane whose weight index falls outside its
+    // filter's window reads a safe address; the value is zeroed when it is consumed (not here, so
+    // that nothing waits on a load right after issuing it).  Each lane reads one whole line.
+    float a[KA];
+    uint32_t am;
+    auto load_a = [&]() {
+        am = 0;
 #pragma unroll
-            for (int s = 0; s < 4; ++s) {
-                const int j = jj + s;
-                a[s] = (fvalid && j >= 0 && j < P.L) ? wk[j] : 0.f;
+        for (int s4 = 0; s4 < KA; s4 += 4) {
+            if (AL4) {
+                const bool in = fvalid && jj >= 0 && jj < P.L;
+                const f32x4u a4 = *(const f32x4u*)(wb + (uint32_t)(in ? (wrow + jj) * 4 : 0));
+#pragma unroll
+                for (int s = 0; s < 4; ++s) a[s4 + s] = a4[s];
+                am |= in ? (0xfu << s4) : 0u;
+            } else {
+#pragma unroll
+                for (int s = 0; s < 4; ++s) {
+                    const int j = jj + s;
+                    const bool in = fvalid && j >= 0 && j < P.L;
+                    a[s4 + s] = *(const float*)(wb + (uint32_t)(in ? (wrow + j) * 4 : 0));
+                    am |= in ? (1u << (s4 + s)) : 0u;
+                }
             }
+            jj += 4;
         }
-        float b[4][CT];
+    };
+    auto load_b = [&](bvec (&bd)[KC]) {
 #pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            const long long roff = (long long)ch * P.HW;
+        for (int s = 0; s < KC; ++s) {
+            if (VEC) {
+                bd[s] = *(const bvec*)(xb + (uint32_t)(xcol[0] + rowofs));
+            } else {
 #pragma unroll
-            for (int c = 0; c < CT; ++c) b[s][c] = xcol[c][roff];
-            ch = (ch + 1 == P.Cin) ? 0 : ch + 1;
+                for (int c = 0; c < CT; ++c) bd[s][c] = *(const float*)(xb + (uint32_t)(xcol[c] + rowofs));
+            }
+            rowofs += plane;
+            rowofs = (rowofs == wrap) ? 0u : rowofs;             // cyclic wrap past channel Cin-1
         }
+    };
+    auto mma = [&](int s0, const bvec (&bs)[KC]) {
 #pragma unroll
-        for (int s = 0; s < 4; ++s)
+        for (int s = 0; s < KC; ++s) {
+            const float av = (am >> (s0 + s)) & 1u ? a[s0 + s] : 0.f;
 #pragma unroll
             for (int c = 0; c < CT; ++c)
-                acc[c] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[s], b[s][c], acc[c], 0, 0, 0);
-        jj += 4;
+                acc[c] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bs[s][c], acc[c], 0, 0, 0);
+        }
+    };
+
+    // K loop: per KA steps one round of A loads; B loads run KC steps ahead of the matrix instructions.
+    static_assert(KA % (2 * KC) == 0, "chunking");
+    bvec b0[KC], b1[KC];
+    load_b(b0);
+    for (int t = 0; t < T.Uh; t += KA) {
+        load_a();
+#pragma unroll
+        for (int s0 = 0; s0 < KA; s0 += 2 * KC) {
+            load_b(b1);
+            mma(s0, b0);
+            if (t + s0 + 2 * KC < T.Uh) load_b(b0);
+            mma(s0 + KC, b1);
+        }
     }
 
     // ---- store: register v of the accumulator holds tile row 8*(v/4) + 4*h + v%4, column f ----
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
         const int fr = 8 * (v >> 2) + 4 * h + (v & 3);
-        const int mr = mb * T.TM + fr / T.TI, ir = ib * T.TI + fr % T.TI;
-        const int kr = (int)(((long long)mr * T.b.inv) % T.b.P) + T.b.P * ir;
-        if (fr / T.TI < T.TM && mr < T.b.P && kr < P.Cout) {
+        const int kr = __shfl(k, fr, 64);            // filter of tile row fr lives in lane fr's registers
+        const bool rvalid = __shfl((int)fvalid, fr, 64) != 0;
+        if (rvalid) {
+            if (VEC) {
+                if (live[0]) {                        // CT divides H*W: the CT columns are live together
+                    bvec o;
 #pragma unroll
-            for (int c = 0; c < CT; ++c)
-                if (live[c]) y[ycol[c] + (long long)kr * P.HW] = acc[c][v];
+                    for (int c = 0; c < CT; ++c) o[c] = acc[c][v];
+                    *(bvec*)(y + (size_t)ycol[0] + (size_t)kr * P.HW) = o;
+                }
+            } else {
+#pragma unroll
+                for (int c = 0; c < CT; ++c)
+                    if (live[c]) y[(size_t)ycol[c] + (size_t)kr * P.HW] = acc[c][v];
+            }
         }
     }
 }
@@ -128,18 +185,10 @@ int pow2_floor(int v)
     return p;
 }
 
-}  // namespace
-
-// Whether the matrix-core forward takes this problem (otherwise the generic kernel does).
-bool forward_mfma_eligible(const Problem& p)
+template <int CT, bool VEC>
+void launch_cfg(const float* x, const float* w, float* y, const Problem& p, hipStream_t st)
 {
-    // enough contraction depth and columns for a 32x32 tile to pay; everything else is exact for any shape
-    return p.L >= 8 && p.NQ >= 64 && p.Cout >= 8;
-}
-
-hipError_t launch_forward_mfma(const float* x, const float* w, float* y, const Problem& p, hipStream_t st)
-{
-    constexpr int CT = 2;
+    constexpr int KC = 8, KA = 32;
     FwdTiling t;
     t.b = make_band(p);
     t.TI = pow2_floor(t.b.F < 32 ? t.b.F : 32);
@@ -147,12 +196,36 @@ hipError_t launch_forward_mfma(const float* x, const float* w, float* y, const P
     t.IB = (t.b.F + t.TI - 1) / t.TI;
     t.MB = (t.b.P + t.TM - 1) / t.TM;
     const int U = p.L + t.b.g * (t.TM - 1);
-    t.Uh = (((U + 1) / 2) + 3) / 4 * 4;
+    t.Uh = (((U + 1) / 2) + KA - 1) / KA * KA;
     const long long nct = (p.NQ + 32 * CT - 1) / (32 * CT);
     t.NCT = (int)((nct + 7) / 8 * 8);
     t.FG = (t.IB * t.MB + 3) / 4;
     const long long blocks = (long long)t.NCT * t.FG;
-    hipLaunchKernelGGL(forward_mfma32<CT>, dim3((unsigned)blocks), dim3(256), 0, st, x, w, y, p, t);
+    const bool al4 = (t.b.g % 4 == 0) && (p.L % 4 == 0);
+    if (al4)
+        forward_mfma32<CT, KC, true, VEC><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(x, w, y, p, t);
+    else
+        forward_mfma32<CT, KC, false, VEC><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(x, w, y, p, t);
+}
+
+}  // namespace
+
+// Whether the matrix-core forward takes this problem (otherwise the generic kernel does).
+bool forward_mfma_eligible(const Problem& p)
+{
+    // enough contraction depth and columns for a 32x32 tile to pay, and byte offsets that fit 32 bits
+    const long long rows = p.Cin > p.Cout ? p.Cin : p.Cout;
+    return p.L >= 8 && p.NQ >= 64 && p.Cout >= 8 && p.Cin < 65536 && (long long)p.NQ * rows * 4 < (1ll << 32) &&
+           (long long)p.Cout * p.L * 4 < (1ll << 31);
+}
+
+hipError_t launch_forward_mfma(const float* x, const float* w, float* y, const Problem& p, hipStream_t st)
+{
+    // 16-byte plane accesses need 16-byte aligned tensors; unaligned views take the scalar-column path
+    if (p.HW % 4 == 0 && (((uintptr_t)x | (uintptr_t)y) & 15u) == 0)
+        launch_cfg<4, true>(x, w, y, p, st);
+    else
+        launch_cfg<2, false>(x, w, y, p, st);
     return hipGetLastError();
 }
 
