@@ -106,6 +106,7 @@ size_t scc_backward_weight_workspace_bytes(int N, int Cin, int Cout, int H, int 
 {
     Problem p;
     if (make_problem(N, Cin, Cout, H, W, cg, co, &p) != SCC_OK || !dtype_ok(dtype)) return 0;
+    if (dtype == SCC_F32 && scc::backward_weight_mfma_eligible(p)) return scc::backward_weight_mfma_workspace(p);
     return 0;
 }
 
@@ -121,8 +122,12 @@ int scc_backward_weight(const void* x, const void* dy, void* dw, int N, int Cin,
     if (need > 0 && (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 255u) != 0))
         return SCC_ERR_WORKSPACE;
     hipStream_t st = (hipStream_t)stream;
-    if (dtype == SCC_F32)
+    if (dtype == SCC_F32) {
+        if (scc::backward_weight_mfma_eligible(p) && (((uintptr_t)x | (uintptr_t)dy) & 15u) == 0)
+            return launch_status(scc::launch_backward_weight_mfma((const float*)x, (const float*)dy, (float*)dw,
+                                                                  (float*)workspace, p, st));
         return launch_status(scc::launch_backward_weight_generic((const float*)x, (const float*)dy, (float*)dw, p, st));
+    }
     return launch_status(
         scc::launch_backward_weight_generic((const scc::bf16_t*)x, (const scc::bf16_t*)dy, (float*)dw, p, st));
 }
