@@ -7,11 +7,13 @@
 // Per tile of 32 filters (TM window starts x TI filters per start, see scc_band.h) and a chunk
 // of 64 span positions u (channel (lo+u) mod Cin), the product D[f][u] = sum_q dy[q,k_f]*x[q,ch(u)]
 // is a GEMM whose contraction runs over the columns q = (n,p).  Both operands are contiguous
-// along p, which is what a lane of the A/B operand wants: each lane reads 16 bytes (4 pixels)
-// of its own row per load, the two half-waves take alternate 16-byte groups, so one plane
-// line is consumed by four back-to-back loads.
+// along p in memory while a lane of the MFMA operand wants successive K values of ONE row, so
+// the rows go through LDS: a wavefront reads 32 columns of its 96 operand rows (32 dy rows,
+// 64 x rows) with fully coalesced 16-byte loads (8 rows x 128 bytes per instruction), parks
+// them in a private, padded LDS block and reads them back in operand layout.  The global loads
+// of the next 32 columns are in flight while the matrix instructions of the current ones issue.
 //
-// The columns are split over workgroups (K-split) and again over the 8 wavefronts of a
+// The columns are split over workgroups (K-split) and again over the 4 wavefronts of a
 // workgroup.  Wavefront partials are summed through LDS in wave order, workgroup partials go to
 // the workspace in the layout of dw and a second kernel sums them in split order: no atomics,
 // bitwise reproducible.
@@ -25,9 +27,10 @@ namespace {
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int kWaves = 8;   // wavefronts per workgroup
+constexpr int kWaves = 4;     // wavefronts per workgroup
 constexpr int kPosTiles = 2;  // span positions per wavefront tile = 32 * kPosTiles
-constexpr int kG = 4;       // 16-byte groups per operand row per pipelined chunk (one 128-byte line per row)
+constexpr int kRows = 32 * (1 + kPosTiles);  // operand rows of a wavefront: 32 of dy, 64 of x
+constexpr int kLd = 36;       // floats per staged row: 32 columns + 4 of padding (bank spread, 16-byte aligned)
 
 struct BwwTiling {
     Band b;
@@ -53,7 +56,9 @@ __global__ __launch_bounds__(kWaves * 64) void backward_weight_mfma32(const floa
                                                                       const float* __restrict__ dy,
                                                                       float* __restrict__ out, Problem P, BwwTiling T)
 {
-    __shared__ float red[kWaves][32][32 * kPosTiles];
+    // per-wavefront staging blocks; reused after the K loop for the cross-wavefront sum
+    __shared__ __attribute__((aligned(16))) float lds[kWaves * kRows * kLd];
+    static_assert(kWaves * kRows * kLd >= kWaves * 32 * 32 * kPosTiles, "reduction buffer must fit the staging area");
 
     // workgroup -> (K-split, tile, span chunk); workgroups of one K-split share blockIdx % 8, i.e. an
     // XCD and its L2: they read the same dy columns and overlapping x windows at about the same time.
@@ -68,20 +73,26 @@ __global__ __launch_bounds__(kWaves * 64) void backward_weight_mfma32(const floa
 
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int lane = threadIdx.x & 63;
-    const int f = lane & 31, h = lane >> 5;
-
-    int k, off;
-    bool fvalid;
-    tile_filter(T, P, mb, ib, f, k, off, fvalid);
+    const int f = lane & 31, h = lane >> 5;   // operand view: row f, half-wave h
+    const int lr = lane >> 3, lc = lane & 7;  // load view: row lr of a group of 8, 16-byte column lc of 8
     const int lo = T.b.g * mb * T.TM;
 
-    // operand rows of this lane: A = dy row k; B[c] = x row of span position sc*64 + c*32 + f
+    // byte offsets (inside one sample) of the 12 rows this lane loads: rows 8*it + lr of the block;
+    // block rows 0..31 are dy rows of the tile's filters, rows 32..95 are x rows of the span chunk
     const uint32_t plane = (uint32_t)P.HW * 4u;
-    const uint32_t rowA = (uint32_t)(fvalid ? k : 0) * plane;
-    uint32_t rowB[kPosTiles];
+    uint32_t rowoff[kRows / 8];
 #pragma unroll
-    for (int c = 0; c < kPosTiles; ++c)
-        rowB[c] = (uint32_t)((lo + sc * (32 * kPosTiles) + c * 32 + f) % P.Cin) * plane;
+    for (int it = 0; it < kRows / 8; ++it) {
+        const int row = 8 * it + lr;
+        if (it < 4) {
+            int k, off;
+            bool valid;
+            tile_filter(T, P, mb, ib, row, k, off, valid);
+            rowoff[it] = (uint32_t)(valid ? k : 0) * plane;      // rows of filters that do not exist are never stored
+        } else {
+            rowoff[it] = (uint32_t)((lo + sc * (32 * kPosTiles) + (row - 32)) % P.Cin) * plane;
+        }
+    }
 
     // column groups [qb, qe) of this wavefront: the K-split's share, split again over the waves
     const long long per_ks = ((long long)T.NQ4 + T.KS - 1) / T.KS;
@@ -89,21 +100,14 @@ __global__ __launch_bounds__(kWaves * 64) void backward_weight_mfma32(const floa
     const long long ks_e = ks_b + per_ks < T.NQ4 ? ks_b + per_ks : T.NQ4;
     const long long span = ks_e > ks_b ? ks_e - ks_b : 0;
     const long long per_w = (span + kWaves - 1) / kWaves;
-    const int qb = (int)(ks_b + (long long)wave * per_w);
-    const int qe = (int)((ks_b + (long long)(wave + 1) * per_w) < ks_e ? (ks_b + (long long)(wave + 1) * per_w) : ks_e);
+    const long long wb_ = ks_b + (long long)wave * per_w, we_ = wb_ + per_w;
+    const int qb = (int)(wb_ < ks_e ? wb_ : ks_e);
+    const int qe = (int)(we_ < ks_e ? we_ : ks_e);
+    const int nchunk = (qe - qb + 7) / 8;     // chunks of 8 groups = 32 columns
 
-    // this half-wave takes groups qb + h, qb + h + 2, ...
-    int qg = qb + h;
-    const uint32_t col = (uint32_t)qg * 4u;                      // first column of the group
-    uint32_t n = col / (uint32_t)P.HW, p = col % (uint32_t)P.HW;
-    uint32_t offA = (n * (uint32_t)P.Cout * (uint32_t)P.HW + p) * 4u;   // without the row
-    uint32_t offB = (n * (uint32_t)P.Cin * (uint32_t)P.HW + p) * 4u;
-    const uint32_t dn = 8u / (uint32_t)P.HW, dp = 8u % (uint32_t)P.HW;    // advance of 8 columns
-    const uint32_t stepA = (dn * (uint32_t)P.Cout * (uint32_t)P.HW + dp) * 4u;
-    const uint32_t stepB = (dn * (uint32_t)P.Cin * (uint32_t)P.HW + dp) * 4u;
-    const uint32_t wrapA = ((uint32_t)P.Cout - 1u) * plane, wrapB = ((uint32_t)P.Cin - 1u) * plane;
     const char* ab = (const char*)dy;
     const char* bb = (const char*)x;
+    float* stage = lds + wave * (kRows * kLd);
 
     f32x16 acc[kPosTiles];
 #pragma unroll
@@ -111,60 +115,58 @@ __global__ __launch_bounds__(kWaves * 64) void backward_weight_mfma32(const floa
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[c][v] = 0.f;
 
-    auto load_chunk = [&](f32x4 (&ad)[kG], f32x4 (&bd)[kG][kPosTiles], uint32_t& vm) {
-        vm = 0;
+    f32x4 r[kRows / 8];
+    bool rin = false;
+    auto load_chunk = [&](int ci) {           // global -> registers, one 16-byte piece of 12 rows
+        const int qg = qb + ci * 8 + lc;      // this lane's column group
+        rin = qg < qe;
+        const uint32_t col = (uint32_t)(rin ? qg : 0) * 4u;
+        const uint32_t n = col / (uint32_t)P.HW, p = col % (uint32_t)P.HW;
+        const uint32_t ca = (n * (uint32_t)P.Cout * (uint32_t)P.HW + p) * 4u;
+        const uint32_t cb = (n * (uint32_t)P.Cin * (uint32_t)P.HW + p) * 4u;
 #pragma unroll
-        for (int s = 0; s < kG; ++s) {
-            const bool in = qg < qe;
-            vm |= in ? (1u << s) : 0u;
-            ad[s] = *(const f32x4*)(ab + (in ? offA + rowA : 0u));
+        for (int it = 0; it < kRows / 8; ++it)
+            r[it] = it < 4 ? *(const f32x4*)(ab + (ca + rowoff[it])) : *(const f32x4*)(bb + (cb + rowoff[it]));
+    };
+    auto park_chunk = [&]() {                 // registers -> LDS (zeros past the end of the range)
 #pragma unroll
-            for (int c = 0; c < kPosTiles; ++c) bd[s][c] = *(const f32x4*)(bb + (in ? offB + rowB[c] : 0u));
-            qg += 2;
-            p += dp;
-            const bool wr = p >= (uint32_t)P.HW;       // crossed into the next sample
-            p -= wr ? (uint32_t)P.HW : 0u;
-            offA += stepA + (wr ? wrapA : 0u);
-            offB += stepB + (wr ? wrapB : 0u);
+        for (int it = 0; it < kRows / 8; ++it) {
+            f32x4 v = r[it];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) v[e] = rin ? v[e] : 0.f;
+            *(f32x4*)(stage + (8 * it + lr) * kLd + 4 * lc) = v;
         }
     };
-    auto mma_chunk = [&](const f32x4 (&as)[kG], const f32x4 (&bs)[kG][kPosTiles], uint32_t vm) {
+    auto mma_chunk = [&]() {                  // LDS -> operand layout -> matrix cores
 #pragma unroll
-        for (int s = 0; s < kG; ++s) {
-            const bool in = (vm >> s) & 1u;          // a group past the end of the range contributes 0 * 0
+        for (int s = 0; s < 4; ++s) {         // half-wave h takes 16-byte column 2*s + h
+            const f32x4 av = *(const f32x4*)(stage + f * kLd + 4 * (2 * s + h));
+            f32x4 bv[kPosTiles];
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const float av = in ? as[s][e] : 0.f;
+            for (int c = 0; c < kPosTiles; ++c) bv[c] = *(const f32x4*)(stage + (32 + 32 * c + f) * kLd + 4 * (2 * s + h));
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
 #pragma unroll
                 for (int c = 0; c < kPosTiles; ++c)
-                    acc[c] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, in ? bs[s][c][e] : 0.f, acc[c], 0, 0, 0);
-            }
+                    acc[c] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[e], bv[c][e], acc[c], 0, 0, 0);
         }
     };
 
-    // each chunk covers 2*kG column groups; an even number of chunks, software pipelined
-    const int groups = qe > qb ? qe - qb : 0;
-    const int nch = ((groups + 2 * kG - 1) / (2 * kG) + 1) / 2 * 2;
-    if (nch > 0) {
-        f32x4 a0[kG], a1[kG], b0[kG][kPosTiles], b1[kG][kPosTiles];
-        uint32_t v0, v1;
-        load_chunk(a0, b0, v0);
-        for (int cix = 0; cix + 2 < nch; cix += 2) {
-            load_chunk(a1, b1, v1);
-            mma_chunk(a0, b0, v0);
-            load_chunk(a0, b0, v0);
-            mma_chunk(a1, b1, v1);
-        }
-        load_chunk(a1, b1, v1);
-        mma_chunk(a0, b0, v0);
-        mma_chunk(a1, b1, v1);
+    if (nchunk > 0) load_chunk(0);
+    for (int ci = 0; ci < nchunk; ++ci) {
+        park_chunk();                          // waits for the loads of chunk ci
+        if (ci + 1 < nchunk) load_chunk(ci + 1);
+        mma_chunk();                           // the LDS block is private to the wavefront: no barrier
     }
+    __syncthreads();                           // everyone is done with the staging blocks
 
     // wavefront partials -> LDS; accumulator register v holds row 8*(v/4) + 4*h + v%4, column f
+    float* red = lds;
 #pragma unroll
     for (int c = 0; c < kPosTiles; ++c)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) red[wave][8 * (v >> 2) + 4 * h + (v & 3)][c * 32 + f] = acc[c][v];
+        for (int v = 0; v < 16; ++v)
+            red[(wave * 32 + 8 * (v >> 2) + 4 * h + (v & 3)) * (32 * kPosTiles) + c * 32 + f] = acc[c][v];
     __syncthreads();
 
     // fixed-order sum over the wavefronts, written in the layout of dw
@@ -173,7 +175,7 @@ __global__ __launch_bounds__(kWaves * 64) void backward_weight_mfma32(const floa
         const int fr = e / (32 * kPosTiles), uc = e % (32 * kPosTiles);
         float s = 0.f;
 #pragma unroll
-        for (int wv = 0; wv < kWaves; ++wv) s += red[wv][fr][uc];
+        for (int wv = 0; wv < kWaves; ++wv) s += red[(wv * 32 + fr) * (32 * kPosTiles) + uc];
         int kr, offr;
         bool vr;
         tile_filter(T, P, mb, ib, fr, kr, offr, vr);
@@ -182,15 +184,30 @@ __global__ __launch_bounds__(kWaves * 64) void backward_weight_mfma32(const floa
     }
 }
 
-// dw[e] = sum over K-splits of part[ks][e], in split order
+// dw[e] = sum over K-splits of part[ks][e].  A workgroup owns 64 weights; its 4 wavefronts take the
+// splits ks = w, w+4, ... (all loads of a thread are independent and in flight together), then the
+// four sums are added in wavefront order: the summation tree is fixed, so results are reproducible.
 __global__ __launch_bounds__(256) void backward_weight_reduce(const float* __restrict__ part, float* __restrict__ dw,
                                                               int count, int KS)
 {
-    const int e = blockIdx.x * 256 + threadIdx.x;
-    if (e >= count) return;
+    __shared__ float sums[4][64];
+    const int el = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int e = blockIdx.x * 64 + el;
     float s = 0.f;
-    for (int ks = 0; ks < KS; ++ks) s += part[(size_t)ks * count + e];
-    dw[e] = s;
+    if (e < count) {
+        int ks = w;
+        for (; ks + 28 < KS; ks += 32) {      // 8 loads in flight per trip
+            float v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = part[(size_t)(ks + 4 * u) * count + e];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) s += v[u];
+        }
+        for (; ks < KS; ks += 4) s += part[(size_t)ks * count + e];
+    }
+    sums[w][el] = s;
+    __syncthreads();
+    if (w == 0 && e < count) dw[e] = ((sums[0][el] + sums[1][el]) + sums[2][el]) + sums[3][el];
 }
 
 int pow2_floor(int v)
@@ -211,10 +228,10 @@ BwwTiling make_tiling(const Problem& p)
     t.U = p.L + t.b.g * (t.TM - 1);
     t.NSC = (t.U + 32 * kPosTiles - 1) / (32 * kPosTiles);
     t.NQ4 = (int)(p.NQ / 4);
-    // enough workgroups to fill 256 CUs about twice, but at least 16 column groups per wavefront
+    // enough workgroups to fill 256 CUs about twice, but at least 32 column groups per wavefront
     const long long tiles = (long long)t.IB * t.MB * t.NSC;
     long long ks = (512 + tiles - 1) / tiles;
-    const long long ks_max = t.NQ4 / (16 * kWaves);
+    const long long ks_max = t.NQ4 / (32 * kWaves);
     if (ks > ks_max) ks = ks_max;
     if (ks < 1) ks = 1;
     t.KS = (int)ks;
@@ -247,7 +264,7 @@ hipError_t launch_backward_weight_mfma(const float* x, const float* dy, float* d
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || t.KS == 1) return e;
     const int count = p.Cout * p.L;
-    backward_weight_reduce<<<dim3((unsigned)((count + 255) / 256)), dim3(256), 0, st>>>(workspace, dw, count, t.KS);
+    backward_weight_reduce<<<dim3((unsigned)((count + 63) / 64)), dim3(256), 0, st>>>(workspace, dw, count, t.KS);
     return hipGetLastError();
 }
 
