@@ -149,12 +149,12 @@ __global__ __launch_bounds__(256) void backward_input_mfma32(const float* __rest
                     bvec o;
 #pragma unroll
                     for (int cc = 0; cc < CT; ++cc) o[cc] = acc[cc][v];
-                    *(bvec*)(dx + (size_t)dcol[0] + (size_t)cr * P.HW) = o;
+                    __builtin_nontemporal_store(o, (bvec*)(dx + (size_t)dcol[0] + (size_t)cr * P.HW));  // written once, not re-read here
                 }
             } else {
 #pragma unroll
                 for (int cc = 0; cc < CT; ++cc)
-                    if (live[cc]) dx[(size_t)dcol[cc] + (size_t)cr * P.HW] = acc[cc][v];
+                    if (live[cc]) __builtin_nontemporal_store(acc[cc][v], dx + (size_t)dcol[cc] + (size_t)cr * P.HW);
             }
         }
     }

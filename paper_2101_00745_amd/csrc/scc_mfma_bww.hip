@@ -30,6 +30,7 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 constexpr int kWaves = 4;     // wavefronts per workgroup
 constexpr int kPosTiles = 2;  // span positions per wavefront tile = 32 * kPosTiles
 constexpr int kRows = 32 * (1 + kPosTiles);  // operand rows of a wavefront: 32 of dy, 64 of x
+constexpr int kDepth = 4;    // chunks of global loads in flight per wavefront
 constexpr int kLd = 36;       // floats per staged row: 32 columns + 4 of padding (bank spread, 16-byte aligned)
 
 struct BwwTiling {
@@ -58,6 +59,7 @@ __global__ __launch_bounds__(kWaves * 64) void backward_weight_mfma32(const floa
 {
     // per-wavefront staging blocks; reused after the K loop for the cross-wavefront sum
     __shared__ __attribute__((aligned(16))) float lds[kWaves * kRows * kLd];
+    __shared__ int row_k[32], row_off[32];     // filter and span offset of each tile row (k = -1: no such filter)
     static_assert(kWaves * kRows * kLd >= kWaves * 32 * 32 * kPosTiles, "reduction buffer must fit the staging area");
 
     // workgroup -> (K-split, tile, span chunk); workgroups of one K-split share blockIdx % 8, i.e. an
@@ -77,20 +79,34 @@ __global__ __launch_bounds__(kWaves * 64) void backward_weight_mfma32(const floa
     const int lr = lane >> 3, lc = lane & 7;  // load view: row lr of a group of 8, 16-byte column lc of 8
     const int lo = T.b.g * mb * T.TM;
 
+    // this lane's tile row: filter k_f (one modulo per lane; other rows' filters come by lane exchange)
+    int k_f, off_f;
+    bool valid_f;
+    tile_filter(T, P, mb, ib, f, k_f, off_f, valid_f);
+    if (threadIdx.x < 32) {
+        row_k[f] = valid_f ? k_f : -1;
+        row_off[f] = off_f;
+    }
+
     // byte offsets (inside one sample) of the 12 rows this lane loads: rows 8*it + lr of the block;
     // block rows 0..31 are dy rows of the tile's filters, rows 32..95 are x rows of the span chunk
     const uint32_t plane = (uint32_t)P.HW * 4u;
     uint32_t rowoff[kRows / 8];
+    const int ksafe = valid_f ? k_f : 0;       // rows of filters that do not exist are loaded but never stored
+    const int cbase = (lo + sc * (32 * kPosTiles)) % P.Cin;
 #pragma unroll
     for (int it = 0; it < kRows / 8; ++it) {
         const int row = 8 * it + lr;
         if (it < 4) {
-            int k, off;
-            bool valid;
-            tile_filter(T, P, mb, ib, row, k, off, valid);
-            rowoff[it] = (uint32_t)(valid ? k : 0) * plane;      // rows of filters that do not exist are never stored
+            rowoff[it] = (uint32_t)__shfl(ksafe, row, 64) * plane;
         } else {
-            rowoff[it] = (uint32_t)((lo + sc * (32 * kPosTiles) + (row - 32)) % P.Cin) * plane;
+            int c = cbase + (row - 32);
+            if (P.Cin >= 32 * kPosTiles) {     // at most one wrap
+                c -= (c >= P.Cin) ? P.Cin : 0;
+            } else {
+                c %= P.Cin;
+            }
+            rowoff[it] = (uint32_t)c * plane;
         }
     }
 
@@ -105,6 +121,21 @@ __global__ __launch_bounds__(kWaves * 64) void backward_weight_mfma32(const floa
     const int qe = (int)(we_ < ks_e ? we_ : ks_e);
     const int nchunk = (qe - qb + 7) / 8;     // chunks of 8 groups = 32 columns
 
+    // this lane's column group in chunk 0, advanced by 8 groups (32 columns) per chunk
+    uint32_t cn, cp;
+    {
+        const uint32_t col = (uint32_t)(qb + lc) * 4u;
+        cn = col / (uint32_t)P.HW;
+        cp = col % (uint32_t)P.HW;
+    }
+    const uint32_t dn = 32u / (uint32_t)P.HW, dp = 32u % (uint32_t)P.HW;
+    uint32_t offA = (cn * (uint32_t)P.Cout * (uint32_t)P.HW + cp) * 4u;
+    uint32_t offB = (cn * (uint32_t)P.Cin * (uint32_t)P.HW + cp) * 4u;
+    const uint32_t stepA = (dn * (uint32_t)P.Cout * (uint32_t)P.HW + dp) * 4u;
+    const uint32_t stepB = (dn * (uint32_t)P.Cin * (uint32_t)P.HW + dp) * 4u;
+    const uint32_t wrapA = ((uint32_t)P.Cout - 1u) * plane, wrapB = ((uint32_t)P.Cin - 1u) * plane;
+    int qnext = qb + lc;                       // column group the next load_chunk call takes
+
     const char* ab = (const char*)dy;
     const char* bb = (const char*)x;
     float* stage = lds + wave * (kRows * kLd);
@@ -115,26 +146,31 @@ __global__ __launch_bounds__(kWaves * 64) void backward_weight_mfma32(const floa
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[c][v] = 0.f;
 
-    f32x4 r[kRows / 8];
-    bool rin = false;
-    auto load_chunk = [&](int ci) {           // global -> registers, one 16-byte piece of 12 rows
-        const int qg = qb + ci * 8 + lc;      // this lane's column group
-        rin = qg < qe;
-        const uint32_t col = (uint32_t)(rin ? qg : 0) * 4u;
-        const uint32_t n = col / (uint32_t)P.HW, p = col % (uint32_t)P.HW;
-        const uint32_t ca = (n * (uint32_t)P.Cout * (uint32_t)P.HW + p) * 4u;
-        const uint32_t cb = (n * (uint32_t)P.Cin * (uint32_t)P.HW + p) * 4u;
+    auto load_chunk = [&](f32x4 (&r)[kRows / 8], bool& rin) {   // global -> registers, 16 bytes of 12 rows
+        rin = qnext < qe;
+        const uint32_t ca = rin ? offA : 0u, cb = rin ? offB : 0u;
 #pragma unroll
         for (int it = 0; it < kRows / 8; ++it)
             r[it] = it < 4 ? *(const f32x4*)(ab + (ca + rowoff[it])) : *(const f32x4*)(bb + (cb + rowoff[it]));
+        qnext += 8;
+        cp += dp;
+        const bool wr = cp >= (uint32_t)P.HW;                    // crossed into the next sample
+        cp -= wr ? (uint32_t)P.HW : 0u;
+        offA += stepA + (wr ? wrapA : 0u);
+        offB += stepB + (wr ? wrapB : 0u);
     };
-    auto park_chunk = [&]() {                 // registers -> LDS (zeros past the end of the range)
+    auto park_chunk = [&](const f32x4 (&r)[kRows / 8], bool rin, bool full) {   // registers -> LDS
+        if (full) {
 #pragma unroll
-        for (int it = 0; it < kRows / 8; ++it) {
-            f32x4 v = r[it];
+            for (int it = 0; it < kRows / 8; ++it) *(f32x4*)(stage + (8 * it + lr) * kLd + 4 * lc) = r[it];
+        } else {                                                 // ragged last chunk: zeros past the range
 #pragma unroll
-            for (int e = 0; e < 4; ++e) v[e] = rin ? v[e] : 0.f;
-            *(f32x4*)(stage + (8 * it + lr) * kLd + 4 * lc) = v;
+            for (int it = 0; it < kRows / 8; ++it) {
+                f32x4 v = r[it];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) v[e] = rin ? v[e] : 0.f;
+                *(f32x4*)(stage + (8 * it + lr) * kLd + 4 * lc) = v;
+            }
         }
     };
     auto mma_chunk = [&]() {                  // LDS -> operand layout -> matrix cores
@@ -152,11 +188,24 @@ __global__ __launch_bounds__(kWaves * 64) void backward_weight_mfma32(const floa
         }
     };
 
-    if (nchunk > 0) load_chunk(0);
-    for (int ci = 0; ci < nchunk; ++ci) {
-        park_chunk();                          // waits for the loads of chunk ci
-        if (ci + 1 < nchunk) load_chunk(ci + 1);
-        mma_chunk();                           // the LDS block is private to the wavefront: no barrier
+    // kDepth chunks of global loads are in flight while the matrix instructions of another issue;
+    // the LDS block is private to the wavefront, so the K loop needs no barrier
+    f32x4 r[kDepth][kRows / 8];
+    bool in[kDepth];
+#pragma unroll
+    for (int d = 0; d < kDepth; ++d) {
+        in[d] = false;
+        if (d < nchunk) load_chunk(r[d], in[d]);
+    }
+    for (int ci = 0; ci < nchunk; ci += kDepth) {
+#pragma unroll
+        for (int d = 0; d < kDepth; ++d) {
+            if (ci + d < nchunk) {
+                park_chunk(r[d], in[d], qb + 8 * (ci + d + 1) <= qe);
+                if (ci + d + kDepth < nchunk) load_chunk(r[d], in[d]);
+                mma_chunk();
+            }
+        }
     }
     __syncthreads();                           // everyone is done with the staging blocks
 
@@ -176,11 +225,9 @@ __global__ __launch_bounds__(kWaves * 64) void backward_weight_mfma32(const floa
         float s = 0.f;
 #pragma unroll
         for (int wv = 0; wv < kWaves; ++wv) s += red[(wv * 32 + fr) * (32 * kPosTiles) + uc];
-        int kr, offr;
-        bool vr;
-        tile_filter(T, P, mb, ib, fr, kr, offr, vr);
-        const int j = sc * (32 * kPosTiles) + uc - offr;
-        if (vr && j >= 0 && j < P.L) dst[(size_t)kr * P.L + j] = s;
+        const int kr = row_k[fr];
+        const int j = sc * (32 * kPosTiles) + uc - row_off[fr];
+        if (kr >= 0 && j >= 0 && j < P.L) dst[(size_t)kr * P.L + j] = s;
     }
 }
 
@@ -228,9 +275,9 @@ BwwTiling make_tiling(const Problem& p)
     t.U = p.L + t.b.g * (t.TM - 1);
     t.NSC = (t.U + 32 * kPosTiles - 1) / (32 * kPosTiles);
     t.NQ4 = (int)(p.NQ / 4);
-    // enough workgroups to fill 256 CUs about twice, but at least 32 column groups per wavefront
+    // about one workgroup per CU (one wavefront per SIMD, deep prefetch), at least 32 column groups per wavefront
     const long long tiles = (long long)t.IB * t.MB * t.NSC;
-    long long ks = (512 + tiles - 1) / tiles;
+    long long ks = (256 + tiles - 1) / tiles;
     const long long ks_max = t.NQ4 / (32 * kWaves);
     if (ks > ks_max) ks = ks_max;
     if (ks < 1) ks = 1;

@@ -167,12 +167,12 @@ __global__ __launch_bounds__(256) void forward_mfma32(const float* __restrict__ 
                     bvec o;
 #pragma unroll
                     for (int c = 0; c < CT; ++c) o[c] = acc[c][v];
-                    *(bvec*)(y + (size_t)ycol[0] + (size_t)kr * P.HW) = o;
+                    __builtin_nontemporal_store(o, (bvec*)(y + (size_t)ycol[0] + (size_t)kr * P.HW));  // written once, not re-read here
                 }
             } else {
 #pragma unroll
                 for (int c = 0; c < CT; ++c)
-                    if (live[c]) y[(size_t)ycol[c] + (size_t)kr * P.HW] = acc[c][v];
+                    if (live[c]) __builtin_nontemporal_store(acc[c][v], y + (size_t)ycol[c] + (size_t)kr * P.HW);
             }
         }
     }
