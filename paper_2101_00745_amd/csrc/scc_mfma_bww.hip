@@ -28,17 +28,20 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kWaves = 4;     // wavefronts per workgroup
-constexpr int kPosTiles = 2;  // span positions per wavefront tile = 32 * kPosTiles
-constexpr int kRows = 32 * (1 + kPosTiles);  // operand rows of a wavefront: 32 of dy, 64 of x
-constexpr int kDepth = 4;    // chunks of global loads in flight per wavefront
 constexpr int kLd = 36;       // floats per staged row: 32 columns + 4 of padding (bank spread, 16-byte aligned)
+
+// NPT = span positions per wavefront tile / 32 (1, 2 or 3): the tile is 32 filters x 32*NPT positions
+constexpr int rows_of(int npt) { return 32 * (1 + npt); }            // operand rows: 32 of dy, 32*NPT of x
+constexpr int depth_of(int npt) { return npt == 3 ? 2 : 4; }         // chunks of global loads in flight
+constexpr size_t lds_bytes_of(int npt) { return (size_t)kWaves * rows_of(npt) * kLd * 4 + 2 * 32 * 4; }
 
 struct BwwTiling {
     Band b;
     int TI, TM;   // tile = TM starts x TI filters per start
     int IB, MB;   // tiles along i and m
     int U;        // span positions of a tile: L + g*(TM-1)
-    int NSC;      // span chunks of 64 positions
+    int NPT;      // span positions per wavefront tile / 32
+    int NSC;      // span chunks of 32*NPT positions
     int KS;       // K-splits (workgroups per tile and span chunk)
     int NQ4;      // groups of 4 consecutive columns: N*HW/4
 };
@@ -53,13 +56,17 @@ __device__ __forceinline__ void tile_filter(const BwwTiling& T, const Problem& P
     off = T.b.g * mi;
 }
 
+template <int kPosTiles>
 __global__ __launch_bounds__(kWaves * 64) void backward_weight_mfma32(const float* __restrict__ x,
                                                                       const float* __restrict__ dy,
                                                                       float* __restrict__ out, Problem P, BwwTiling T)
 {
-    // per-wavefront staging blocks; reused after the K loop for the cross-wavefront sum
-    __shared__ __attribute__((aligned(16))) float lds[kWaves * kRows * kLd];
-    __shared__ int row_k[32], row_off[32];     // filter and span offset of each tile row (k = -1: no such filter)
+    constexpr int kRows = rows_of(kPosTiles), kDepth = depth_of(kPosTiles);
+    // per-wavefront staging blocks, reused after the K loop for the cross-wavefront sum; then the filter
+    // and span offset of each tile row (k = -1: no such filter)
+    extern __shared__ __attribute__((aligned(16))) float lds[];
+    int* row_k = (int*)(lds + kWaves * kRows * kLd);
+    int* row_off = row_k + 32;
     static_assert(kWaves * kRows * kLd >= kWaves * 32 * 32 * kPosTiles, "reduction buffer must fit the staging area");
 
     // workgroup -> (K-split, tile, span chunk); workgroups of one K-split share blockIdx % 8, i.e. an
@@ -273,7 +280,18 @@ BwwTiling make_tiling(const Problem& p)
     t.IB = (t.b.F + t.TI - 1) / t.TI;
     t.MB = (t.b.P + t.TM - 1) / t.TM;
     t.U = p.L + t.b.g * (t.TM - 1);
-    t.NSC = (t.U + 32 * kPosTiles - 1) / (32 * kPosTiles);
+    // positions per wavefront tile: the fewest operand rows over all span chunks, ties to the smaller tile
+    t.NPT = 1;
+    long long best = -1;
+    for (int npt = 1; npt <= 3; ++npt) {
+        const long long chunks = (t.U + 32 * npt - 1) / (32 * npt);
+        const long long rows = chunks * (1 + npt);
+        if (best < 0 || rows < best) {
+            best = rows;
+            t.NPT = npt;
+        }
+    }
+    t.NSC = (t.U + 32 * t.NPT - 1) / (32 * t.NPT);
     t.NQ4 = (int)(p.NQ / 4);
     // about one workgroup per CU (one wavefront per SIMD, deep prefetch), at least 32 column groups per wavefront
     const long long tiles = (long long)t.IB * t.MB * t.NSC;
@@ -307,8 +325,21 @@ hipError_t launch_backward_weight_mfma(const float* x, const float* dy, float* d
     const long long ntile = (long long)t.IB * t.MB * t.NSC;
     const long long blocks = (long long)((t.KS + 7) / 8 * 8) * ntile;
     float* out = t.KS > 1 ? workspace : dw;
-    backward_weight_mfma32<<<dim3((unsigned)blocks), dim3(kWaves * 64), 0, st>>>(x, dy, out, p, t);
-    hipError_t e = hipGetLastError();
+    const dim3 grid((unsigned)blocks), block(kWaves * 64);
+    hipError_t e = hipSuccess;
+    if (t.NPT == 1) {
+        backward_weight_mfma32<1><<<grid, block, lds_bytes_of(1), st>>>(x, dy, out, p, t);
+    } else if (t.NPT == 2) {
+        backward_weight_mfma32<2><<<grid, block, lds_bytes_of(2), st>>>(x, dy, out, p, t);
+    } else {
+        // more than 64 KiB of LDS per workgroup has to be allowed once per process
+        static const hipError_t allowed = hipFuncSetAttribute((const void*)backward_weight_mfma32<3>,
+                                                              hipFuncAttributeMaxDynamicSharedMemorySize,
+                                                              (int)lds_bytes_of(3));
+        if (allowed != hipSuccess) return allowed;
+        backward_weight_mfma32<3><<<grid, block, lds_bytes_of(3), st>>>(x, dy, out, p, t);
+    }
+    e = hipGetLastError();
     if (e != hipSuccess || t.KS == 1) return e;
     const int count = p.Cout * p.L;
     backward_weight_reduce<<<dim3((unsigned)((count + 63) / 64)), dim3(256), 0, st>>>(workspace, dw, count, t.KS);

@@ -40,7 +40,7 @@ __global__ __launch_bounds__(256) void forward_mfma32(const float* __restrict__ 
                                                       float* __restrict__ y, Problem P, FwdTiling T)
 {
     typedef float bvec __attribute__((ext_vector_type(CT)));
-    constexpr int KA = 32;  // K-steps per chunk of A loads: 32 consecutive weights = one 128-byte line per lane
+    constexpr int KA = 2 * KC;  // K-steps per round of A loads: 16 consecutive weights = half a 128-byte line per lane
 
     // workgroup -> (column tile, filter-tile group); all groups of a column tile share blockIdx % 8,
     // i.e. one XCD and its L2, because they re-read the same channel planes.
@@ -140,19 +140,16 @@ __global__ __launch_bounds__(256) void forward_mfma32(const float* __restrict__ 
         }
     };
 
-    // K loop: per KA steps one round of A loads; B loads run KC steps ahead of the matrix instructions.
-    static_assert(KA % (2 * KC) == 0, "chunking");
+    // K loop over rounds of KA = 2*KC steps: one round of A loads, B loads KC steps ahead of the
+    // matrix instructions.  Uh is a multiple of KA.
     bvec b0[KC], b1[KC];
     load_b(b0);
     for (int t = 0; t < T.Uh; t += KA) {
         load_a();
-#pragma unroll
-        for (int s0 = 0; s0 < KA; s0 += 2 * KC) {
-            load_b(b1);
-            mma(s0, b0);
-            if (t + s0 + 2 * KC < T.Uh) load_b(b0);
-            mma(s0 + KC, b1);
-        }
+        load_b(b1);
+        mma(0, b0);
+        if (t + KA < T.Uh) load_b(b0);
+        mma(KC, b1);
     }
 
     // ---- store: register v of the accumulator holds tile row 8*(v/4) + 4*h + v%4, column f ----
@@ -188,7 +185,7 @@ int pow2_floor(int v)
 template <int CT, bool VEC>
 void launch_cfg(const float* x, const float* w, float* y, const Problem& p, hipStream_t st)
 {
-    constexpr int KC = 8, KA = 32;
+    constexpr int KC = 8;
     FwdTiling t;
     t.b = make_band(p);
     t.TI = pow2_floor(t.b.F < 32 ? t.b.F : 32);
@@ -196,7 +193,7 @@ void launch_cfg(const float* x, const float* w, float* y, const Problem& p, hipS
     t.IB = (t.b.F + t.TI - 1) / t.TI;
     t.MB = (t.b.P + t.TM - 1) / t.TM;
     const int U = p.L + t.b.g * (t.TM - 1);
-    t.Uh = (((U + 1) / 2) + KA - 1) / KA * KA;
+    t.Uh = (((U + 1) / 2) + 2 * KC - 1) / (2 * KC) * (2 * KC);
     const long long nct = (p.NQ + 32 * CT - 1) / (32 * CT);
     t.NCT = (int)((nct + 7) / 8 * 8);
     t.FG = (t.IB * t.MB + 3) / 4;
