@@ -80,6 +80,9 @@ int scc_forward(const void* x, const void* w, void* y, int N, int Cin, int Cout,
             return launch_status(scc::launch_forward_mfma((const float*)x, (const float*)w, (float*)y, p, st));
         return launch_status(scc::launch_forward_generic((const float*)x, (const float*)w, (float*)y, p, st));
     }
+    if (scc::forward_mfma_eligible(p))
+        return launch_status(
+            scc::launch_forward_mfma((const scc::bf16_t*)x, (const scc::bf16_t*)w, (scc::bf16_t*)y, p, st));
     return launch_status(
         scc::launch_forward_generic((const scc::bf16_t*)x, (const scc::bf16_t*)w, (scc::bf16_t*)y, p, st));
 }
@@ -98,6 +101,9 @@ int scc_backward_input(const void* dy, const void* w, void* dx, int N, int Cin, 
             return launch_status(scc::launch_backward_input_mfma((const float*)dy, (const float*)w, (float*)dx, p, st));
         return launch_status(scc::launch_backward_input_generic((const float*)dy, (const float*)w, (float*)dx, p, st));
     }
+    if (scc::backward_input_mfma_eligible(p))
+        return launch_status(
+            scc::launch_backward_input_mfma((const scc::bf16_t*)dy, (const scc::bf16_t*)w, (scc::bf16_t*)dx, p, st));
     return launch_status(
         scc::launch_backward_input_generic((const scc::bf16_t*)dy, (const scc::bf16_t*)w, (scc::bf16_t*)dx, p, st));
 }
@@ -106,7 +112,7 @@ size_t scc_backward_weight_workspace_bytes(int N, int Cin, int Cout, int H, int 
 {
     Problem p;
     if (make_problem(N, Cin, Cout, H, W, cg, co, &p) != SCC_OK || !dtype_ok(dtype)) return 0;
-    if (dtype == SCC_F32 && scc::backward_weight_mfma_eligible(p)) return scc::backward_weight_mfma_workspace(p);
+    if (scc::backward_weight_mfma_eligible(p)) return scc::backward_weight_mfma_workspace(p);
     return 0;
 }
 
@@ -128,6 +134,9 @@ int scc_backward_weight(const void* x, const void* dy, void* dw, int N, int Cin,
                                                                   (float*)workspace, p, st));
         return launch_status(scc::launch_backward_weight_generic((const float*)x, (const float*)dy, (float*)dw, p, st));
     }
+    if (scc::backward_weight_mfma_eligible(p) && (((uintptr_t)x | (uintptr_t)dy) & 7u) == 0)
+        return launch_status(scc::launch_backward_weight_mfma((const scc::bf16_t*)x, (const scc::bf16_t*)dy, (float*)dw,
+                                                              (float*)workspace, p, st));
     return launch_status(
         scc::launch_backward_weight_generic((const scc::bf16_t*)x, (const scc::bf16_t*)dy, (float*)dw, p, st));
 }

@@ -39,12 +39,13 @@ template <typename T> hipError_t launch_backward_weight_generic(const T* x, cons
 
 // Matrix-core (fp32 MFMA) kernels: scc_mfma_*.hip
 bool forward_mfma_eligible(const Problem& p);
-hipError_t launch_forward_mfma(const float* x, const float* w, float* y, const Problem& p, hipStream_t st);
+template <typename T> hipError_t launch_forward_mfma(const T* x, const T* w, T* y, const Problem& p, hipStream_t st);
 bool backward_input_mfma_eligible(const Problem& p);
-hipError_t launch_backward_input_mfma(const float* dy, const float* w, float* dx, const Problem& p, hipStream_t st);
+template <typename T> hipError_t launch_backward_input_mfma(const T* dy, const T* w, T* dx, const Problem& p, hipStream_t st);
 bool backward_weight_mfma_eligible(const Problem& p);
 size_t backward_weight_mfma_workspace(const Problem& p);  // bytes of K-split partials (0 when not split)
-hipError_t launch_backward_weight_mfma(const float* x, const float* dy, float* dw, float* workspace, const Problem& p,
+template <typename T>
+hipError_t launch_backward_weight_mfma(const T* x, const T* dy, float* dw, float* workspace, const Problem& p,
                                        hipStream_t st);
 
 }  // namespace scc

@@ -33,11 +33,13 @@ __device__ __forceinline__ int floor_div(int a, int b)  // b > 0
     return (a % b != 0 && a < 0) ? q - 1 : q;
 }
 
-template <int CT, int KC, bool VEC>
-__global__ __launch_bounds__(256) void backward_input_mfma32(const float* __restrict__ dy, const float* __restrict__ w,
-                                                             float* __restrict__ dx, Problem P, BwiTiling T)
+// T_ is the storage type of dy, w, dx (float or bf16_t); arithmetic is binary32 either way.
+template <typename T_, int CT, int KC, bool VEC>
+__global__ __launch_bounds__(256) void backward_input_mfma32(const T_* __restrict__ dy, const T_* __restrict__ w,
+                                                             T_* __restrict__ dx, Problem P, BwiTiling T)
 {
-    typedef float bvec __attribute__((ext_vector_type(CT)));
+    typedef T_ bvec __attribute__((ext_vector_type(CT)));
+    constexpr uint32_t ES = sizeof(T_);
     const int bid = blockIdx.x;
     const int xcd = bid & 7, slot = bid >> 3;
     const int ct = (slot / T.FG) * 8 + xcd;
@@ -67,7 +69,7 @@ __global__ __launch_bounds__(256) void backward_input_mfma32(const float* __rest
         live[cc] = q < (uint32_t)P.NQ;
         const uint32_t qq = live[cc] ? q : 0u;
         const uint32_t n = qq / (uint32_t)P.HW, p = qq % (uint32_t)P.HW;
-        gcol[cc] = (n * (uint32_t)P.Cout * (uint32_t)P.HW + p) * 4u;
+        gcol[cc] = (n * (uint32_t)P.Cout * (uint32_t)P.HW + p) * ES;
         dcol[cc] = n * (uint32_t)P.Cin * (uint32_t)P.HW + p;
     }
 
@@ -78,7 +80,7 @@ __global__ __launch_bounds__(256) void backward_input_mfma32(const float* __rest
     if (mw < 0) mw += T.b.P;
     int r = (int)(((uint32_t)mw * (uint32_t)T.b.inv) % (uint32_t)T.b.P);   // residue class owning window mw
     int ju = c - T.b.g * (mlo + mm);             // position of channel c inside that window (unwrapped)
-    const uint32_t plane = (uint32_t)P.HW * 4u;
+    const uint32_t plane = (uint32_t)P.HW * ES;
 
     f32x16 acc[CT];
 #pragma unroll
@@ -86,21 +88,21 @@ __global__ __launch_bounds__(256) void backward_input_mfma32(const float* __rest
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[cc][v] = 0.f;
 
-    auto load_chunk = [&](float (&ad)[KC], uint32_t& am, bvec (&bd)[KC]) {
+    auto load_chunk = [&](T_ (&ad)[KC], uint32_t& am, bvec (&bd)[KC]) {
         am = 0;
 #pragma unroll
         for (int s = 0; s < KC; ++s) {
             const int k = r + T.b.P * i;
             const bool kvalid = (mm < M) && (k < P.Cout);
             const bool in = kvalid && cvalid && ju >= 0 && ju < P.L;
-            ad[s] = *(const float*)(wb + (uint32_t)(in ? (k * P.L + ju) * 4 : 0));
+            ad[s] = *(const T_*)(wb + (uint32_t)(in ? (k * P.L + ju) : 0) * ES);
             am |= in ? (1u << s) : 0u;
             const uint32_t rowofs = (uint32_t)(kvalid ? k : 0) * plane;
             if (VEC) {
                 bd[s] = *(const bvec*)(gb + (uint32_t)(gcol[0] + rowofs));
             } else {
 #pragma unroll
-                for (int cc = 0; cc < CT; ++cc) bd[s][cc] = *(const float*)(gb + (uint32_t)(gcol[cc] + rowofs));
+                for (int cc = 0; cc < CT; ++cc) bd[s][cc] = *(const T_*)(gb + (uint32_t)(gcol[cc] + rowofs));
             }
             // next slot: next filter of this window, or the first filter of the next window
             ++i;
@@ -113,18 +115,18 @@ __global__ __launch_bounds__(256) void backward_input_mfma32(const float* __rest
             r = nextw ? rn : r;
         }
     };
-    auto mma_chunk = [&](const float (&as)[KC], uint32_t am, const bvec (&bs)[KC]) {
+    auto mma_chunk = [&](const T_ (&as)[KC], uint32_t am, const bvec (&bs)[KC]) {
 #pragma unroll
         for (int s = 0; s < KC; ++s) {
-            const float av = (am >> s) & 1u ? as[s] : 0.f;
+            const float av = (am >> s) & 1u ? to_f32(as[s]) : 0.f;
 #pragma unroll
             for (int cc = 0; cc < CT; ++cc)
-                acc[cc] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bs[s][cc], acc[cc], 0, 0, 0);
+                acc[cc] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, to_f32((T_)bs[s][cc]), acc[cc], 0, 0, 0);
         }
     };
 
     // software pipelined over an even number of chunks (Uh is a multiple of 2*KC)
-    float a0[KC], a1[KC];
+    T_ a0[KC], a1[KC];
     bvec b0[KC], b1[KC];
     uint32_t m0, m1;
     const int nch = Uh / KC;
@@ -148,20 +150,20 @@ __global__ __launch_bounds__(256) void backward_input_mfma32(const float* __rest
                 if (live[0]) {
                     bvec o;
 #pragma unroll
-                    for (int cc = 0; cc < CT; ++cc) o[cc] = acc[cc][v];
+                    for (int cc = 0; cc < CT; ++cc) o[cc] = from_f32<T_>(acc[cc][v]);
                     __builtin_nontemporal_store(o, (bvec*)(dx + (size_t)dcol[0] + (size_t)cr * P.HW));  // written once, not re-read here
                 }
             } else {
 #pragma unroll
                 for (int cc = 0; cc < CT; ++cc)
-                    if (live[cc]) __builtin_nontemporal_store(acc[cc][v], dx + (size_t)dcol[cc] + (size_t)cr * P.HW);
+                    if (live[cc]) __builtin_nontemporal_store(from_f32<T_>(acc[cc][v]), dx + (size_t)dcol[cc] + (size_t)cr * P.HW);
             }
         }
     }
 }
 
-template <int CT, bool VEC>
-void launch_cfg(const float* dy, const float* w, float* dx, const Problem& p, hipStream_t st)
+template <typename T_, int CT, bool VEC>
+void launch_cfg(const T_* dy, const T_* w, T_* dx, const Problem& p, hipStream_t st)
 {
     constexpr int KC = 8;
     BwiTiling t;
@@ -171,7 +173,7 @@ void launch_cfg(const float* dy, const float* w, float* dx, const Problem& p, hi
     t.NCT = (int)((nct + 7) / 8 * 8);
     t.FG = (t.CB + 3) / 4;
     const long long blocks = (long long)t.NCT * t.FG;
-    backward_input_mfma32<CT, KC, VEC><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(dy, w, dx, p, t);
+    backward_input_mfma32<T_, CT, KC, VEC><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(dy, w, dx, p, t);
 }
 
 }  // namespace
@@ -186,13 +188,17 @@ bool backward_input_mfma_eligible(const Problem& p)
            (long long)p.Cout * p.L * 4 < (1ll << 31);
 }
 
-hipError_t launch_backward_input_mfma(const float* dy, const float* w, float* dx, const Problem& p, hipStream_t st)
+template <typename T_>
+hipError_t launch_backward_input_mfma(const T_* dy, const T_* w, T_* dx, const Problem& p, hipStream_t st)
 {
-    if (p.HW % 4 == 0 && (((uintptr_t)dy | (uintptr_t)dx) & 15u) == 0)
-        launch_cfg<4, true>(dy, w, dx, p, st);
+    if (p.HW % 4 == 0 && (((uintptr_t)dy | (uintptr_t)dx) & (4 * sizeof(T_) - 1)) == 0)
+        launch_cfg<T_, 4, true>(dy, w, dx, p, st);
     else
-        launch_cfg<2, false>(dy, w, dx, p, st);
+        launch_cfg<T_, 2, false>(dy, w, dx, p, st);
     return hipGetLastError();
 }
+
+template hipError_t launch_backward_input_mfma<float>(const float*, const float*, float*, const Problem&, hipStream_t);
+template hipError_t launch_backward_input_mfma<bf16_t>(const bf16_t*, const bf16_t*, bf16_t*, const Problem&, hipStream_t);
 
 }  // namespace scc

@@ -56,11 +56,14 @@ __device__ __forceinline__ void tile_filter(const BwwTiling& T, const Problem& P
     off = T.b.g * mi;
 }
 
-template <int kPosTiles>
-__global__ __launch_bounds__(kWaves * 64) void backward_weight_mfma32(const float* __restrict__ x,
-                                                                      const float* __restrict__ dy,
+// T_ is the storage type of x and dy (float or bf16_t); staged values, products, sums and dw are binary32.
+template <typename T_, int kPosTiles>
+__global__ __launch_bounds__(kWaves * 64) void backward_weight_mfma32(const T_* __restrict__ x,
+                                                                      const T_* __restrict__ dy,
                                                                       float* __restrict__ out, Problem P, BwwTiling T)
 {
+    typedef T_ ldvec __attribute__((ext_vector_type(4)));   // 4 consecutive columns of one row, as stored
+    constexpr uint32_t ES = sizeof(T_);
     constexpr int kRows = rows_of(kPosTiles), kDepth = depth_of(kPosTiles);
     // per-wavefront staging blocks, reused after the K loop for the cross-wavefront sum; then the filter
     // and span offset of each tile row (k = -1: no such filter)
@@ -97,7 +100,7 @@ __global__ __launch_bounds__(kWaves * 64) void backward_weight_mfma32(const floa
 
     // byte offsets (inside one sample) of the 12 rows this lane loads: rows 8*it + lr of the block;
     // block rows 0..31 are dy rows of the tile's filters, rows 32..95 are x rows of the span chunk
-    const uint32_t plane = (uint32_t)P.HW * 4u;
+    const uint32_t plane = (uint32_t)P.HW * ES;
     uint32_t rowoff[kRows / 8];
     const int ksafe = valid_f ? k_f : 0;       // rows of filters that do not exist are loaded but never stored
     const int cbase = (lo + sc * (32 * kPosTiles)) % P.Cin;
@@ -136,10 +139,10 @@ __global__ __launch_bounds__(kWaves * 64) void backward_weight_mfma32(const floa
         cp = col % (uint32_t)P.HW;
     }
     const uint32_t dn = 32u / (uint32_t)P.HW, dp = 32u % (uint32_t)P.HW;
-    uint32_t offA = (cn * (uint32_t)P.Cout * (uint32_t)P.HW + cp) * 4u;
-    uint32_t offB = (cn * (uint32_t)P.Cin * (uint32_t)P.HW + cp) * 4u;
-    const uint32_t stepA = (dn * (uint32_t)P.Cout * (uint32_t)P.HW + dp) * 4u;
-    const uint32_t stepB = (dn * (uint32_t)P.Cin * (uint32_t)P.HW + dp) * 4u;
+    uint32_t offA = (cn * (uint32_t)P.Cout * (uint32_t)P.HW + cp) * ES;
+    uint32_t offB = (cn * (uint32_t)P.Cin * (uint32_t)P.HW + cp) * ES;
+    const uint32_t stepA = (dn * (uint32_t)P.Cout * (uint32_t)P.HW + dp) * ES;
+    const uint32_t stepB = (dn * (uint32_t)P.Cin * (uint32_t)P.HW + dp) * ES;
     const uint32_t wrapA = ((uint32_t)P.Cout - 1u) * plane, wrapB = ((uint32_t)P.Cin - 1u) * plane;
     int qnext = qb + lc;                       // column group the next load_chunk call takes
 
@@ -153,12 +156,12 @@ __global__ __launch_bounds__(kWaves * 64) void backward_weight_mfma32(const floa
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[c][v] = 0.f;
 
-    auto load_chunk = [&](f32x4 (&r)[kRows / 8], bool& rin) {   // global -> registers, 16 bytes of 12 rows
+    auto load_chunk = [&](ldvec (&r)[kRows / 8], bool& rin) {   // global -> registers, 4 columns of each row
         rin = qnext < qe;
         const uint32_t ca = rin ? offA : 0u, cb = rin ? offB : 0u;
 #pragma unroll
         for (int it = 0; it < kRows / 8; ++it)
-            r[it] = it < 4 ? *(const f32x4*)(ab + (ca + rowoff[it])) : *(const f32x4*)(bb + (cb + rowoff[it]));
+            r[it] = it < 4 ? *(const ldvec*)(ab + (ca + rowoff[it])) : *(const ldvec*)(bb + (cb + rowoff[it]));
         qnext += 8;
         cp += dp;
         const bool wr = cp >= (uint32_t)P.HW;                    // crossed into the next sample
@@ -166,16 +169,21 @@ __global__ __launch_bounds__(kWaves * 64) void backward_weight_mfma32(const floa
         offA += stepA + (wr ? wrapA : 0u);
         offB += stepB + (wr ? wrapB : 0u);
     };
-    auto park_chunk = [&](const f32x4 (&r)[kRows / 8], bool rin, bool full) {   // registers -> LDS
+    auto park_chunk = [&](const ldvec (&r)[kRows / 8], bool rin, bool full) {   // registers -> LDS, widened
         if (full) {
 #pragma unroll
-            for (int it = 0; it < kRows / 8; ++it) *(f32x4*)(stage + (8 * it + lr) * kLd + 4 * lc) = r[it];
+            for (int it = 0; it < kRows / 8; ++it) {
+                f32x4 v;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) v[e] = to_f32((T_)r[it][e]);
+                *(f32x4*)(stage + (8 * it + lr) * kLd + 4 * lc) = v;
+            }
         } else {                                                 // ragged last chunk: zeros past the range
 #pragma unroll
             for (int it = 0; it < kRows / 8; ++it) {
-                f32x4 v = r[it];
+                f32x4 v;
 #pragma unroll
-                for (int e = 0; e < 4; ++e) v[e] = rin ? v[e] : 0.f;
+                for (int e = 0; e < 4; ++e) v[e] = rin ? to_f32((T_)r[it][e]) : 0.f;
                 *(f32x4*)(stage + (8 * it + lr) * kLd + 4 * lc) = v;
             }
         }
@@ -197,7 +205,7 @@ __global__ __launch_bounds__(kWaves * 64) void backward_weight_mfma32(const floa
 
     // kDepth chunks of global loads are in flight while the matrix instructions of another issue;
     // the LDS block is private to the wavefront, so the K loop needs no barrier
-    f32x4 r[kDepth][kRows / 8];
+    ldvec r[kDepth][kRows / 8];
     bool in[kDepth];
 #pragma unroll
     for (int d = 0; d < kDepth; ++d) {
@@ -318,7 +326,8 @@ size_t backward_weight_mfma_workspace(const Problem& p)
     return t.KS > 1 ? (size_t)t.KS * p.Cout * p.L * sizeof(float) : 0;
 }
 
-hipError_t launch_backward_weight_mfma(const float* x, const float* dy, float* dw, float* workspace, const Problem& p,
+template <typename T_>
+hipError_t launch_backward_weight_mfma(const T_* x, const T_* dy, float* dw, float* workspace, const Problem& p,
                                        hipStream_t st)
 {
     const BwwTiling t = make_tiling(p);
@@ -328,16 +337,16 @@ hipError_t launch_backward_weight_mfma(const float* x, const float* dy, float* d
     const dim3 grid((unsigned)blocks), block(kWaves * 64);
     hipError_t e = hipSuccess;
     if (t.NPT == 1) {
-        backward_weight_mfma32<1><<<grid, block, lds_bytes_of(1), st>>>(x, dy, out, p, t);
+        backward_weight_mfma32<T_, 1><<<grid, block, lds_bytes_of(1), st>>>(x, dy, out, p, t);
     } else if (t.NPT == 2) {
-        backward_weight_mfma32<2><<<grid, block, lds_bytes_of(2), st>>>(x, dy, out, p, t);
+        backward_weight_mfma32<T_, 2><<<grid, block, lds_bytes_of(2), st>>>(x, dy, out, p, t);
     } else {
         // more than 64 KiB of LDS per workgroup has to be allowed once per process
-        static const hipError_t allowed = hipFuncSetAttribute((const void*)backward_weight_mfma32<3>,
+        static const hipError_t allowed = hipFuncSetAttribute((const void*)backward_weight_mfma32<T_, 3>,
                                                               hipFuncAttributeMaxDynamicSharedMemorySize,
                                                               (int)lds_bytes_of(3));
         if (allowed != hipSuccess) return allowed;
-        backward_weight_mfma32<3><<<grid, block, lds_bytes_of(3), st>>>(x, dy, out, p, t);
+        backward_weight_mfma32<T_, 3><<<grid, block, lds_bytes_of(3), st>>>(x, dy, out, p, t);
     }
     e = hipGetLastError();
     if (e != hipSuccess || t.KS == 1) return e;
@@ -345,5 +354,10 @@ hipError_t launch_backward_weight_mfma(const float* x, const float* dy, float* d
     backward_weight_reduce<<<dim3((unsigned)((count + 63) / 64)), dim3(256), 0, st>>>(workspace, dw, count, t.KS);
     return hipGetLastError();
 }
+
+template hipError_t launch_backward_weight_mfma<float>(const float*, const float*, float*, float*, const Problem&,
+                                                       hipStream_t);
+template hipError_t launch_backward_weight_mfma<bf16_t>(const bf16_t*, const bf16_t*, float*, float*, const Problem&,
+                                                        hipStream_t);
 
 }  // namespace scc

@@ -35,11 +35,15 @@ struct FwdTiling {
 // AL4  g and L are multiples of 4: groups of four weights are wholly inside or outside a window
 // VEC  H*W is a multiple of CT: a lane owns CT CONSECUTIVE columns (one CT*4-byte load per plane,
 //      one CT*4-byte store per output row); otherwise a lane owns columns f, f+32, ...
-template <int CT, int KC, bool AL4, bool VEC>
-__global__ __launch_bounds__(256) void forward_mfma32(const float* __restrict__ x, const float* __restrict__ w,
-                                                      float* __restrict__ y, Problem P, FwdTiling T)
+// T    storage type of x, w, y (float or bf16_t); products and sums are binary32 either way: bf16
+//      values are widened in registers and go through the same fp32 matrix instruction
+template <typename T_, int CT, int KC, bool AL4, bool VEC>
+__global__ __launch_bounds__(256) void forward_mfma32(const T_* __restrict__ x, const T_* __restrict__ w,
+                                                      T_* __restrict__ y, Problem P, FwdTiling T)
 {
-    typedef float bvec __attribute__((ext_vector_type(CT)));
+    typedef T_ bvec __attribute__((ext_vector_type(CT)));               // CT consecutive columns of one plane
+    typedef T_ avec __attribute__((ext_vector_type(4), aligned(sizeof(T_))));  // 4 consecutive weights
+    constexpr uint32_t ES = sizeof(T_);
     constexpr int KA = 2 * KC;  // K-steps per round of A loads: 16 consecutive weights = half a 128-byte line per lane
 
     // workgroup -> (column tile, filter-tile group); all groups of a column tile share blockIdx % 8,
@@ -76,10 +80,10 @@ __global__ __launch_bounds__(256) void forward_mfma32(const float* __restrict__ 
         live[c] = q < (uint32_t)P.NQ;
         const uint32_t qq = live[c] ? q : 0u;
         const uint32_t n = qq / (uint32_t)P.HW, p = qq % (uint32_t)P.HW;
-        xcol[c] = (n * (uint32_t)P.Cin * (uint32_t)P.HW + p) * 4u;
+        xcol[c] = (n * (uint32_t)P.Cin * (uint32_t)P.HW + p) * ES;
         ycol[c] = n * (uint32_t)P.Cout * (uint32_t)P.HW + p;
     }
-    const uint32_t plane = (uint32_t)P.HW * 4u;                  // bytes between channel planes
+    const uint32_t plane = (uint32_t)P.HW * ES;                  // bytes between channel planes
     const uint32_t wrap = (uint32_t)P.Cin * plane;               // bytes of one sample's channels
     uint32_t rowofs = (uint32_t)((lo + h * T.Uh) % P.Cin) * plane;  // plane this half-wave reads next
     int jj = h * T.Uh - off;                                     // weight index this lane reads next
@@ -93,7 +97,7 @@ __global__ __launch_bounds__(256) void forward_mfma32(const float* __restrict__ 
     // A operands of KA K-steps.  Loads are branch free: a lane whose weight index falls outside its
     // filter's window reads a safe address; the value is zeroed when it is consumed (not here, so
     // that nothing waits on a load right after issuing it).  Each lane reads one whole line.
-    float a[KA];
+    T_ a[KA];
     uint32_t am;
     auto load_a = [&]() {
         am = 0;
@@ -101,7 +105,7 @@ __global__ __launch_bounds__(256) void forward_mfma32(const float* __restrict__ 
         for (int s4 = 0; s4 < KA; s4 += 4) {
             if (AL4) {
                 const bool in = fvalid && jj >= 0 && jj < P.L;
-                const f32x4u a4 = *(const f32x4u*)(wb + (uint32_t)(in ? (wrow + jj) * 4 : 0));
+                const avec a4 = *(const avec*)(wb + (uint32_t)(in ? (wrow + jj) : 0) * ES);
 #pragma unroll
                 for (int s = 0; s < 4; ++s) a[s4 + s] = a4[s];
                 am |= in ? (0xfu << s4) : 0u;
@@ -110,7 +114,7 @@ __global__ __launch_bounds__(256) void forward_mfma32(const float* __restrict__ 
                 for (int s = 0; s < 4; ++s) {
                     const int j = jj + s;
                     const bool in = fvalid && j >= 0 && j < P.L;
-                    a[s4 + s] = *(const float*)(wb + (uint32_t)(in ? (wrow + j) * 4 : 0));
+                    a[s4 + s] = *(const T_*)(wb + (uint32_t)(in ? (wrow + j) : 0) * ES);
                     am |= in ? (1u << (s4 + s)) : 0u;
                 }
             }
@@ -124,7 +128,7 @@ __global__ __launch_bounds__(256) void forward_mfma32(const float* __restrict__ 
                 bd[s] = *(const bvec*)(xb + (uint32_t)(xcol[0] + rowofs));
             } else {
 #pragma unroll
-                for (int c = 0; c < CT; ++c) bd[s][c] = *(const float*)(xb + (uint32_t)(xcol[c] + rowofs));
+                for (int c = 0; c < CT; ++c) bd[s][c] = *(const T_*)(xb + (uint32_t)(xcol[c] + rowofs));
             }
             rowofs += plane;
             rowofs = (rowofs == wrap) ? 0u : rowofs;             // cyclic wrap past channel Cin-1
@@ -133,10 +137,10 @@ __global__ __launch_bounds__(256) void forward_mfma32(const float* __restrict__ 
     auto mma = [&](int s0, const bvec (&bs)[KC]) {
 #pragma unroll
         for (int s = 0; s < KC; ++s) {
-            const float av = (am >> (s0 + s)) & 1u ? a[s0 + s] : 0.f;
+            const float av = (am >> (s0 + s)) & 1u ? to_f32(a[s0 + s]) : 0.f;
 #pragma unroll
             for (int c = 0; c < CT; ++c)
-                acc[c] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bs[s][c], acc[c], 0, 0, 0);
+                acc[c] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, to_f32((T_)bs[s][c]), acc[c], 0, 0, 0);
         }
     };
 
@@ -163,13 +167,13 @@ __global__ __launch_bounds__(256) void forward_mfma32(const float* __restrict__ 
                 if (live[0]) {                        // CT divides H*W: the CT columns are live together
                     bvec o;
 #pragma unroll
-                    for (int c = 0; c < CT; ++c) o[c] = acc[c][v];
+                    for (int c = 0; c < CT; ++c) o[c] = from_f32<T_>(acc[c][v]);
                     __builtin_nontemporal_store(o, (bvec*)(y + (size_t)ycol[0] + (size_t)kr * P.HW));  // written once, not re-read here
                 }
             } else {
 #pragma unroll
                 for (int c = 0; c < CT; ++c)
-                    if (live[c]) __builtin_nontemporal_store(acc[c][v], y + (size_t)ycol[c] + (size_t)kr * P.HW);
+                    if (live[c]) __builtin_nontemporal_store(from_f32<T_>(acc[c][v]), y + (size_t)ycol[c] + (size_t)kr * P.HW);
             }
         }
     }
@@ -182,8 +186,8 @@ int pow2_floor(int v)
     return p;
 }
 
-template <int CT, bool VEC>
-void launch_cfg(const float* x, const float* w, float* y, const Problem& p, hipStream_t st)
+template <typename T_, int CT, bool VEC>
+void launch_cfg(const T_* x, const T_* w, T_* y, const Problem& p, hipStream_t st)
 {
     constexpr int KC = 8;
     FwdTiling t;
@@ -200,9 +204,9 @@ void launch_cfg(const float* x, const float* w, float* y, const Problem& p, hipS
     const long long blocks = (long long)t.NCT * t.FG;
     const bool al4 = (t.b.g % 4 == 0) && (p.L % 4 == 0);
     if (al4)
-        forward_mfma32<CT, KC, true, VEC><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(x, w, y, p, t);
+        forward_mfma32<T_, CT, KC, true, VEC><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(x, w, y, p, t);
     else
-        forward_mfma32<CT, KC, false, VEC><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(x, w, y, p, t);
+        forward_mfma32<T_, CT, KC, false, VEC><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(x, w, y, p, t);
 }
 
 }  // namespace
@@ -216,14 +220,19 @@ bool forward_mfma_eligible(const Problem& p)
            (long long)p.Cout * p.L * 4 < (1ll << 31);
 }
 
-hipError_t launch_forward_mfma(const float* x, const float* w, float* y, const Problem& p, hipStream_t st)
+template <typename T_>
+hipError_t launch_forward_mfma(const T_* x, const T_* w, T_* y, const Problem& p, hipStream_t st)
 {
-    // 16-byte plane accesses need 16-byte aligned tensors; unaligned views take the scalar-column path
-    if (p.HW % 4 == 0 && (((uintptr_t)x | (uintptr_t)y) & 15u) == 0)
-        launch_cfg<4, true>(x, w, y, p, st);
+    // vector plane accesses (4 columns) need tensors aligned to the vector; unaligned views and planes
+    // whose size is not a multiple of 4 take the scalar-column path
+    if (p.HW % 4 == 0 && (((uintptr_t)x | (uintptr_t)y | (uintptr_t)w) & (4 * sizeof(T_) - 1)) == 0)
+        launch_cfg<T_, 4, true>(x, w, y, p, st);
     else
-        launch_cfg<2, false>(x, w, y, p, st);
+        launch_cfg<T_, 2, false>(x, w, y, p, st);
     return hipGetLastError();
 }
+
+template hipError_t launch_forward_mfma<float>(const float*, const float*, float*, const Problem&, hipStream_t);
+template hipError_t launch_forward_mfma<bf16_t>(const bf16_t*, const bf16_t*, bf16_t*, const Problem&, hipStream_t);
 
 }  // namespace scc
