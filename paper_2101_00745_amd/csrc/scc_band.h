@@ -42,12 +42,17 @@ inline Band make_band(const Problem& p)
         b.g = (int)band_gcd(p.stride, p.Cin);
         b.P = p.Cin / b.g;
         const int q = (p.stride / b.g) % b.P;  // coprime to P
-        int inv = 0;
-        for (int t = 0; t < b.P; ++t)  // P <= Cin: a host loop of at most a few thousand steps
-            if ((int)(((long long)q * t) % b.P) == 1 % b.P) {
-                inv = t;
-                break;
-            }
+        // extended Euclid: q * inv == 1 (mod P)
+        long long r0 = b.P, r1 = q, t0 = 0, t1 = 1;
+        while (r1 != 0) {
+            const long long d = r0 / r1;
+            const long long r2 = r0 - d * r1, t2 = t0 - d * t1;
+            r0 = r1;
+            r1 = r2;
+            t0 = t1;
+            t1 = t2;
+        }
+        int inv = (int)(((t0 % b.P) + b.P) % b.P);  // P == 1: q == 0 and inv == 0
         b.inv = inv;
     }
     b.F = (p.Cout + b.P - 1) / b.P;

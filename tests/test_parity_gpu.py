@@ -198,3 +198,78 @@ def test_non_default_stream(S):
         y = S.scc_forward(xd, wd, layer.cg, layer.co)
     st.synchronize()
     assert rel_err(host(y), O.forward(x, w, layer.cg, layer.co)) <= 2e-5
+
+
+def test_random_sweep_matrix_core_shapes(S):
+    """Shapes the tiled matrix-core kernels accept (window of 8+ channels, hundreds of columns), with
+    ragged column tiles, partial filter tiles, banded and dense windows, wraps; fp32 and bf16."""
+    rng = np.random.default_rng(7452101)
+    for i in range(36):
+        cg = int(rng.choice([1, 2, 3, 4, 8]))
+        L = int(rng.choice([8, 12, 16, 20, 24, 32, 40, 48, 64, 96]))
+        Cin = cg * L
+        Cout = int(rng.integers(8, 200))
+        H, W = int(rng.integers(2, 15)), int(rng.integers(2, 15))
+        if i % 3 == 0:
+            W = 4 * max(1, W // 4)            # H*W a multiple of 4: vector plane accesses
+        N = int(rng.integers(2, 9))
+        co = float(rng.choice([0.0, 0.125, 0.25, 1 / 3, 0.33, 0.5, 0.625, 0.75, 0.9, 1.0]))
+        layer = small("mc%d" % i, N, Cin, Cout, H, W, cg, co)
+        check_layer(S, layer, torch.bfloat16 if i % 4 == 3 else torch.float32, seed_offset=100 + i)
+
+
+def test_unaligned_tensor_views(S):
+    """Tensors that start 4 bytes into an allocation: the 16-byte plane accesses must not be used."""
+    layer = small("unaligned", 3, 64, 96, 8, 8, 2, 0.5)
+    x, w, dy = Wk.make_inputs(layer)
+
+    def shifted(a):
+        buf = torch.empty(a.size + 1, dtype=torch.float32, device="cuda")
+        v = buf[1:].view(a.shape)
+        v.copy_(torch.from_numpy(a))
+        assert v.data_ptr() % 16 == 4 and v.is_contiguous()
+        return v
+
+    xd, wd, dyd = shifted(x), shifted(w), shifted(dy)
+    y = torch.empty(layer.N * layer.Cout * layer.HW + 1, dtype=torch.float32, device="cuda")[1:].view(
+        layer.N, layer.Cout, layer.H, layer.W)
+    dx = torch.empty(x.size + 1, dtype=torch.float32, device="cuda")[1:].view(x.shape)
+    S.scc_forward(xd, wd, layer.cg, layer.co, out=y)
+    S.scc_backward_input(dyd, wd, layer.Cin, layer.cg, layer.co, out=dx)
+    dw = S.scc_backward_weight(xd, dyd, layer.cg, layer.co)
+    assert rel_err(host(y), O.forward(x, w, layer.cg, layer.co)) <= 2e-5
+    assert rel_err(host(dx), O.backward_input(dy, w, layer.Cin, layer.cg, layer.co)) <= 2e-5
+    assert rel_err(host(dw), O.backward_weight(x, dy, layer.cg, layer.co)) <= 2e-5
+
+
+def test_workspace_contract(S):
+    import ctypes
+    layer = Wk.METRIC
+    need = S.scc_backward_weight_workspace_bytes(layer.N, layer.Cin, layer.Cout, layer.H, layer.W, layer.cg, layer.co)
+    assert need > 0 and need % 4 == 0
+    x, w, dy = Wk.make_inputs(layer)
+    xd, dyd = to_dev(x, torch.float32), to_dev(dy, torch.float32)
+    dw = torch.empty(layer.Cout, layer.L, device="cuda")
+    lib = S.load()
+    shape = (layer.N, layer.Cin, layer.Cout, layer.H, layer.W, layer.cg, layer.co, 0)
+    small_ws = torch.empty(need - 4, dtype=torch.uint8, device="cuda")
+    # too small, missing, misaligned: rejected on the host, dw untouched
+    dw.fill_(7.0)
+    assert lib.scc_backward_weight(xd.data_ptr(), dyd.data_ptr(), dw.data_ptr(), *shape, small_ws.data_ptr(),
+                                   need - 4, None) == -5
+    assert lib.scc_backward_weight(xd.data_ptr(), dyd.data_ptr(), dw.data_ptr(), *shape, None, 0, None) == -5
+    big = torch.empty(need + 512, dtype=torch.uint8, device="cuda")
+    assert lib.scc_backward_weight(xd.data_ptr(), dyd.data_ptr(), dw.data_ptr(), *shape, big.data_ptr() + 4,
+                                   need, None) == -5
+    torch.cuda.synchronize()
+    assert bool((dw == 7.0).all())
+    # workspace full of NaN beforehand: contents before the call must not matter
+    ws = torch.full((need // 4,), float("nan"), dtype=torch.float32, device="cuda")
+    got = S.scc_backward_weight(xd, dyd, layer.cg, layer.co, workspace=ws.view(torch.uint8))
+    assert rel_err(host(got), O.backward_weight(x, dy, layer.cg, layer.co)) <= 2e-5
+
+
+@pytest.mark.parametrize("layer", [Wk.STACK[0], Wk.STACK[3], Wk.STACK[6], Wk.STACK[12], Wk.METRIC_SWEEP[1]],
+                         ids=lambda l: l.name)
+def test_bf16_more_layers(S, layer):
+    check_layer(S, layer, torch.bfloat16)
