@@ -32,7 +32,7 @@ constexpr int kLd = 36;       // floats per staged row: 32 columns + 4 of paddin
 
 // NPT = span positions per wavefront tile / 32 (1, 2 or 3): the tile is 32 filters x 32*NPT positions
 constexpr int rows_of(int npt) { return 32 * (1 + npt); }            // operand rows: 32 of dy, 32*NPT of x
-constexpr int depth_of(int npt) { return npt == 3 ? 2 : 4; }         // chunks of global loads in flight
+constexpr int depth_of(int) { return 1; }   // chunks of global loads in flight per wavefront: more only queue up
 constexpr size_t lds_bytes_of(int npt) { return (size_t)kWaves * rows_of(npt) * kLd * 4 + 2 * 32 * 4; }
 
 struct BwwTiling {
@@ -44,6 +44,7 @@ struct BwwTiling {
     int NSC;      // span chunks of 32*NPT positions
     int KS;       // K-splits (workgroups per tile and span chunk)
     int NQ4;      // groups of 4 consecutive columns: N*HW/4
+    int per_ks;   // column groups per K-split: ceil(NQ4 / KS)
 };
 
 __device__ __forceinline__ void tile_filter(const BwwTiling& T, const Problem& P, int mb, int ib, int f, int& k,
@@ -121,14 +122,12 @@ __global__ __launch_bounds__(kWaves * 64) void backward_weight_mfma32(const T_* 
     }
 
     // column groups [qb, qe) of this wavefront: the K-split's share, split again over the waves
-    const long long per_ks = ((long long)T.NQ4 + T.KS - 1) / T.KS;
-    const long long ks_b = (long long)ks * per_ks;
-    const long long ks_e = ks_b + per_ks < T.NQ4 ? ks_b + per_ks : T.NQ4;
-    const long long span = ks_e > ks_b ? ks_e - ks_b : 0;
-    const long long per_w = (span + kWaves - 1) / kWaves;
-    const long long wb_ = ks_b + (long long)wave * per_w, we_ = wb_ + per_w;
-    const int qb = (int)(wb_ < ks_e ? wb_ : ks_e);
-    const int qe = (int)(we_ < ks_e ? we_ : ks_e);
+    const int ks_b = ks * T.per_ks < T.NQ4 ? ks * T.per_ks : T.NQ4;          // NQ4 + per_ks fits an int
+    const int ks_e = ks_b + T.per_ks < T.NQ4 ? ks_b + T.per_ks : T.NQ4;
+    const int per_w = (ks_e - ks_b + kWaves - 1) / kWaves;
+    const int wb_ = ks_b + wave * per_w, we_ = wb_ + per_w;
+    const int qb = wb_ < ks_e ? wb_ : ks_e;
+    const int qe = we_ < ks_e ? we_ : ks_e;
     const int nchunk = (qe - qb + 7) / 8;     // chunks of 8 groups = 32 columns
 
     // this lane's column group in chunk 0, advanced by 8 groups (32 columns) per chunk
@@ -204,7 +203,9 @@ __global__ __launch_bounds__(kWaves * 64) void backward_weight_mfma32(const T_* 
     };
 
     // kDepth chunks of global loads are in flight while the matrix instructions of another issue;
-    // the LDS block is private to the wavefront, so the K loop needs no barrier
+    // the LDS block is private to the wavefront, so the K loop needs no barrier.  (Measured: with
+    // 48 KB per wavefront queued the first data arrives ~6 us after issue whatever the wait policy,
+    // so a batch of kDepth chunks is waited for as a whole.)
     ldvec r[kDepth][kRows / 8];
     bool in[kDepth];
 #pragma unroll
@@ -279,6 +280,21 @@ int pow2_floor(int v)
     return p;
 }
 
+template <typename T_, int NPT>
+hipError_t launch_tile(dim3 grid, dim3 block, hipStream_t st, const T_* x, const T_* dy, float* out, const Problem& p,
+                       const BwwTiling& t)
+{
+    if (lds_bytes_of(NPT) > 64 * 1024) {
+        // more than 64 KiB of LDS per workgroup has to be allowed once (per process: the library drives one GPU)
+        static const hipError_t allowed = hipFuncSetAttribute((const void*)backward_weight_mfma32<T_, NPT>,
+                                                              hipFuncAttributeMaxDynamicSharedMemorySize,
+                                                              (int)lds_bytes_of(NPT));
+        if (allowed != hipSuccess) return allowed;
+    }
+    backward_weight_mfma32<T_, NPT><<<grid, block, lds_bytes_of(NPT), st>>>(x, dy, out, p, t);
+    return hipGetLastError();
+}
+
 BwwTiling make_tiling(const Problem& p)
 {
     BwwTiling t;
@@ -308,6 +324,7 @@ BwwTiling make_tiling(const Problem& p)
     if (ks > ks_max) ks = ks_max;
     if (ks < 1) ks = 1;
     t.KS = (int)ks;
+    t.per_ks = (t.NQ4 + t.KS - 1) / t.KS;
     return t;
 }
 
@@ -336,18 +353,13 @@ hipError_t launch_backward_weight_mfma(const T_* x, const T_* dy, float* dw, flo
     float* out = t.KS > 1 ? workspace : dw;
     const dim3 grid((unsigned)blocks), block(kWaves * 64);
     hipError_t e = hipSuccess;
-    if (t.NPT == 1) {
-        backward_weight_mfma32<T_, 1><<<grid, block, lds_bytes_of(1), st>>>(x, dy, out, p, t);
-    } else if (t.NPT == 2) {
-        backward_weight_mfma32<T_, 2><<<grid, block, lds_bytes_of(2), st>>>(x, dy, out, p, t);
-    } else {
-        // more than 64 KiB of LDS per workgroup has to be allowed once per process
-        static const hipError_t allowed = hipFuncSetAttribute((const void*)backward_weight_mfma32<T_, 3>,
-                                                              hipFuncAttributeMaxDynamicSharedMemorySize,
-                                                              (int)lds_bytes_of(3));
-        if (allowed != hipSuccess) return allowed;
-        backward_weight_mfma32<T_, 3><<<grid, block, lds_bytes_of(3), st>>>(x, dy, out, p, t);
-    }
+    if (t.NPT == 1)
+        e = launch_tile<T_, 1>(grid, block, st, x, dy, out, p, t);
+    else if (t.NPT == 2)
+        e = launch_tile<T_, 2>(grid, block, st, x, dy, out, p, t);
+    else
+        e = launch_tile<T_, 3>(grid, block, st, x, dy, out, p, t);
+    if (e != hipSuccess) return e;
     e = hipGetLastError();
     if (e != hipSuccess || t.KS == 1) return e;
     const int count = p.Cout * p.L;
