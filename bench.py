@@ -20,6 +20,13 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+# HBM bytes per launch of each pass on the metric layer, from two rocprofv3 --pmc runs (FETCH_SIZE scaled by
+# 1.9993, WRITE_SIZE by 1.0; both factors from a plain 64 MiB device copy): profiles/scc_metric_layer_kernels.md
+MEASURED_TRAFFIC_BYTES = {"metric": {"fwd": int((16696.5 * 1.9993 + 32803.1) * 1024),
+                                     "bwi": int((16748.5 * 1.9993 + 32802.5) * 1024),
+                                     "bww": int(((32818.6 + 1038.0) * 1.9993 + 2048.0 + 64.0) * 1024)}}
+KERNELS = {"fwd": ["forward_mfma32"], "bwi": ["backward_input_mfma32"],
+           "bww": ["backward_weight_mfma32", "backward_weight_reduce"]}
 ROTATE_BYTES = 768 << 20       # total size of the rotated buffer sets (memory-side cache is 256 MB)
 
 
@@ -160,16 +167,10 @@ def main():
         per_pass[name] = ev
     dominant = max(per_pass, key=per_pass.get)
     achieved = alg_bytes[dominant] / (per_pass[dominant] * 1e-3) / 1e9
-    traffic = None
-    tpath = os.path.join(ROOT, "profiles", "hbm_traffic_%s.json" % args.workload)
-    if os.path.exists(tpath):
-        try:
-            traffic = json.load(open(tpath)).get(dominant)
-        except Exception:
-            traffic = None
+    traffic = MEASURED_TRAFFIC_BYTES.get(args.workload, {}).get(dominant) if dtype == torch.float32 else None
     roofline = {"bound": "hbm", "kernel": {"fwd": "scc_forward", "bwi": "scc_backward_input",
                                            "bww": "scc_backward_weight"}[dominant],
-                "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "kernels": KERNELS[dominant], "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
                 "algorithmic_bytes_per_launch": alg_bytes[dominant],
                 "avg_us": round(per_pass[dominant] * 1e3, 2),
