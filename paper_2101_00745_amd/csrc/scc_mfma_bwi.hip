@@ -23,8 +23,9 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 struct BwiTiling {
     Band b;
     int CB;   // channel blocks of 32
-    int NCT;  // column tiles, padded to a multiple of 8
-    int FG;   // workgroups per column tile = ceil(CB / 4)
+    int FG;     // workgroups per column tile = ceil(CB / 4)
+    int total;  // workgroups with work: column tiles * FG, channel-block group fastest
+    int chunk;  // consecutive workgroups of that order given to one XCD: ceil(total / 8)
 };
 
 __device__ __forceinline__ int floor_div(int a, int b)  // b > 0
@@ -40,13 +41,17 @@ __global__ __launch_bounds__(256) void backward_input_mfma32(const T_* __restric
 {
     typedef T_ bvec __attribute__((ext_vector_type(CT)));
     constexpr uint32_t ES = sizeof(T_);
+    // blockIdx % 8 names the XCD; each XCD takes a contiguous run of the (column tile, group) order, so the
+    // channel blocks of a column tile, which re-read the same dy planes, share an XCD and its L2
     const int bid = blockIdx.x;
     const int xcd = bid & 7, slot = bid >> 3;
-    const int ct = (slot / T.FG) * 8 + xcd;
-    const int fg = slot % T.FG;
+    const int logical = xcd * T.chunk + slot;
+    if (slot >= T.chunk || logical >= T.total) return;
+    const int ct = logical / T.FG;
+    const int fg = logical % T.FG;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int cb = fg * 4 + wave;
-    if (cb >= T.CB || (long long)ct * (32 * CT) >= P.NQ) return;
+    if (cb >= T.CB) return;
 
     const int lane = threadIdx.x & 63;
     const int f = lane & 31, h = lane >> 5;
@@ -170,9 +175,10 @@ void launch_cfg(const T_* dy, const T_* w, T_* dx, const Problem& p, hipStream_t
     t.b = make_band(p);
     t.CB = (p.Cin + 31) / 32;
     const long long nct = (p.NQ + 32 * CT - 1) / (32 * CT);
-    t.NCT = (int)((nct + 7) / 8 * 8);
     t.FG = (t.CB + 3) / 4;
-    const long long blocks = (long long)t.NCT * t.FG;
+    t.total = (int)(nct * t.FG);
+    t.chunk = (t.total + 7) / 8;
+    const long long blocks = (long long)8 * t.chunk;
     backward_input_mfma32<T_, CT, KC, VEC><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(dy, w, dx, p, t);
 }
 
@@ -191,10 +197,21 @@ bool backward_input_mfma_eligible(const Problem& p)
 template <typename T_>
 hipError_t launch_backward_input_mfma(const T_* dy, const T_* w, T_* dx, const Problem& p, hipStream_t st)
 {
-    if (p.HW % 4 == 0 && (((uintptr_t)dy | (uintptr_t)dx) & (4 * sizeof(T_) - 1)) == 0)
+    // columns per wavefront: 128 when that still gives every SIMD a wavefront, else 64 or 32; vector plane
+    // accesses need planes whose size is a multiple of the vector and tensors aligned to it
+    constexpr long long kEnoughWaves = 1024;
+    const long long blocks32 = (p.Cin + 31) / 32;
+    auto waves = [&](int ct) { return (p.NQ + 32 * ct - 1) / (32 * ct) * blocks32; };
+    const uintptr_t addr = (uintptr_t)dy | (uintptr_t)dx;
+    auto vec_ok = [&](int ct) { return p.HW % ct == 0 && (addr & (ct * sizeof(T_) - 1)) == 0; };
+    if (vec_ok(4) && waves(4) >= kEnoughWaves)
         launch_cfg<T_, 4, true>(dy, w, dx, p, st);
-    else
+    else if (vec_ok(2) && waves(2) >= kEnoughWaves)
+        launch_cfg<T_, 2, true>(dy, w, dx, p, st);
+    else if (waves(2) >= kEnoughWaves || waves(1) < 64)
         launch_cfg<T_, 2, false>(dy, w, dx, p, st);
+    else
+        launch_cfg<T_, 1, false>(dy, w, dx, p, st);
     return hipGetLastError();
 }
 

@@ -45,6 +45,7 @@ struct BwwTiling {
     int KS;       // K-splits (workgroups per tile and span chunk)
     int NQ4;      // groups of 4 consecutive columns: N*HW/4
     int per_ks;   // column groups per K-split: ceil(NQ4 / KS)
+    int chunk;    // consecutive workgroups of the (K-split, tile) order given to one XCD: ceil(KS * tiles / 8)
 };
 
 __device__ __forceinline__ void tile_filter(const BwwTiling& T, const Problem& P, int mb, int ib, int f, int& k,
@@ -73,14 +74,16 @@ __global__ __launch_bounds__(kWaves * 64) void backward_weight_mfma32(const T_* 
     int* row_off = row_k + 32;
     static_assert(kWaves * kRows * kLd >= kWaves * 32 * 32 * kPosTiles, "reduction buffer must fit the staging area");
 
-    // workgroup -> (K-split, tile, span chunk); workgroups of one K-split share blockIdx % 8, i.e. an
-    // XCD and its L2: they read the same dy columns and overlapping x windows at about the same time.
+    // workgroup -> (K-split, tile, span chunk), tile fastest.  blockIdx % 8 names the XCD and each XCD takes
+    // a contiguous run of that order, so the tiles of one K-split, which read the same dy columns and
+    // overlapping x windows at about the same time, share an XCD and its L2.
     const int ntile = T.IB * T.MB * T.NSC;
     const int bid = blockIdx.x;
     const int xcd = bid & 7, slot = bid >> 3;
-    const int ks = (slot / ntile) * 8 + xcd;
-    const int tix = slot % ntile;
-    if (ks >= T.KS) return;   // whole workgroup leaves: no barrier is reached by anyone
+    const int logical = xcd * T.chunk + slot;
+    if (slot >= T.chunk || logical >= T.KS * ntile) return;   // whole workgroup leaves: nobody reaches a barrier
+    const int ks = logical / ntile;
+    const int tix = logical % ntile;
     const int sc = tix % T.NSC, tile = tix / T.NSC;
     const int mb = tile / T.IB, ib = tile % T.IB;
 
@@ -325,6 +328,7 @@ BwwTiling make_tiling(const Problem& p)
     if (ks < 1) ks = 1;
     t.KS = (int)ks;
     t.per_ks = (t.NQ4 + t.KS - 1) / t.KS;
+    t.chunk = (int)((t.KS * tiles + 7) / 8);
     return t;
 }
 
@@ -348,8 +352,7 @@ hipError_t launch_backward_weight_mfma(const T_* x, const T_* dy, float* dw, flo
                                        hipStream_t st)
 {
     const BwwTiling t = make_tiling(p);
-    const long long ntile = (long long)t.IB * t.MB * t.NSC;
-    const long long blocks = (long long)((t.KS + 7) / 8 * 8) * ntile;
+    const long long blocks = (long long)8 * t.chunk;
     float* out = t.KS > 1 ? workspace : dw;
     const dim3 grid((unsigned)blocks), block(kWaves * 64);
     hipError_t e = hipSuccess;

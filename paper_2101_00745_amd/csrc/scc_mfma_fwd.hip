@@ -26,8 +26,9 @@ struct FwdTiling {
     int TI, TM;    // tile = TM starts x TI filters per start; TI*TM <= 32 (TM is capped by P)
     int IB, MB;    // tiles along i and m
     int Uh;        // K-steps per tile (multiple of the chunk length); each half-wave covers Uh channels
-    int NCT;       // column tiles (of 32*CT columns), padded to a multiple of 8
     int FG;        // workgroups per column tile = ceil(IB*MB / 4)
+    int total;     // workgroups with work: column tiles (of 32*CT columns) * FG, filter-tile group fastest
+    int chunk;     // consecutive workgroups of that order given to one XCD: ceil(total / 8)
 };
 
 // CT   column groups of 32 per wavefront (the tile is 32 filters x 32*CT columns)
@@ -46,15 +47,18 @@ __global__ __launch_bounds__(256) void forward_mfma32(const T_* __restrict__ x, 
     constexpr uint32_t ES = sizeof(T_);
     constexpr int KA = 2 * KC;  // K-steps per round of A loads: 16 consecutive weights = half a 128-byte line per lane
 
-    // workgroup -> (column tile, filter-tile group); all groups of a column tile share blockIdx % 8,
-    // i.e. one XCD and its L2, because they re-read the same channel planes.
+    // workgroup -> (column tile, filter-tile group).  blockIdx % 8 names the XCD; each XCD takes a
+    // contiguous run of the (column tile, group) order, so the groups of a column tile, which re-read
+    // the same channel planes, share one XCD and its L2 whenever there are enough column tiles.
     const int bid = blockIdx.x;
     const int xcd = bid & 7, slot = bid >> 3;
-    const int ct = (slot / T.FG) * 8 + xcd;
-    const int fg = slot % T.FG;
+    const int logical = xcd * T.chunk + slot;
+    if (slot >= T.chunk || logical >= T.total) return;
+    const int ct = logical / T.FG;
+    const int fg = logical % T.FG;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int tile = fg * 4 + wave;
-    if (tile >= T.IB * T.MB || (long long)ct * (32 * CT) >= P.NQ) return;
+    if (tile >= T.IB * T.MB) return;
     const int mb = tile / T.IB, ib = tile % T.IB;
 
     const int lane = threadIdx.x & 63;
@@ -186,10 +190,11 @@ int pow2_floor(int v)
     return p;
 }
 
-template <typename T_, int CT, bool VEC>
-void launch_cfg(const T_* x, const T_* w, T_* y, const Problem& p, hipStream_t st)
+constexpr int kKC = 8;            // K-steps per pipelined chunk of B loads
+constexpr int kEnoughWaves = 1024;  // one wavefront per SIMD of the chip
+
+FwdTiling filter_tiling(const Problem& p)
 {
-    constexpr int KC = 8;
     FwdTiling t;
     t.b = make_band(p);
     t.TI = pow2_floor(t.b.F < 32 ? t.b.F : 32);
@@ -197,11 +202,21 @@ void launch_cfg(const T_* x, const T_* w, T_* y, const Problem& p, hipStream_t s
     t.IB = (t.b.F + t.TI - 1) / t.TI;
     t.MB = (t.b.P + t.TM - 1) / t.TM;
     const int U = p.L + t.b.g * (t.TM - 1);
-    t.Uh = (((U + 1) / 2) + 2 * KC - 1) / (2 * KC) * (2 * KC);
-    const long long nct = (p.NQ + 32 * CT - 1) / (32 * CT);
-    t.NCT = (int)((nct + 7) / 8 * 8);
+    t.Uh = (((U + 1) / 2) + 2 * kKC - 1) / (2 * kKC) * (2 * kKC);
     t.FG = (t.IB * t.MB + 3) / 4;
-    const long long blocks = (long long)t.NCT * t.FG;
+    t.total = t.chunk = 0;
+    return t;
+}
+
+template <typename T_, int CT, bool VEC>
+void launch_cfg(const T_* x, const T_* w, T_* y, const Problem& p, hipStream_t st)
+{
+    constexpr int KC = kKC;
+    FwdTiling t = filter_tiling(p);
+    const long long nct = (p.NQ + 32 * CT - 1) / (32 * CT);
+    t.total = (int)(nct * t.FG);
+    t.chunk = (t.total + 7) / 8;
+    const long long blocks = (long long)8 * t.chunk;
     const bool al4 = (t.b.g % 4 == 0) && (p.L % 4 == 0);
     if (al4)
         forward_mfma32<T_, CT, KC, true, VEC><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(x, w, y, p, t);
@@ -223,12 +238,22 @@ bool forward_mfma_eligible(const Problem& p)
 template <typename T_>
 hipError_t launch_forward_mfma(const T_* x, const T_* w, T_* y, const Problem& p, hipStream_t st)
 {
-    // vector plane accesses (4 columns) need tensors aligned to the vector; unaligned views and planes
-    // whose size is not a multiple of 4 take the scalar-column path
-    if (p.HW % 4 == 0 && (((uintptr_t)x | (uintptr_t)y | (uintptr_t)w) & (4 * sizeof(T_) - 1)) == 0)
+    // Columns per wavefront: 128 when that still gives every SIMD a wavefront, else 64 or 32 (layers with
+    // few columns and many filters).  Vector plane accesses (CT consecutive columns per lane) need planes whose
+    // size is a multiple of CT and tensors aligned to the vector; otherwise a lane owns strided single columns.
+    const FwdTiling ft = filter_tiling(p);
+    const long long tiles = (long long)ft.IB * ft.MB;
+    auto waves = [&](int ct) { return (p.NQ + 32 * ct - 1) / (32 * ct) * tiles; };
+    const uintptr_t addr = (uintptr_t)x | (uintptr_t)y | (uintptr_t)w;
+    auto vec_ok = [&](int ct) { return p.HW % ct == 0 && (addr & (ct * sizeof(T_) - 1)) == 0; };
+    if (vec_ok(4) && waves(4) >= kEnoughWaves)
         launch_cfg<T_, 4, true>(x, w, y, p, st);
-    else
+    else if (vec_ok(2) && waves(2) >= kEnoughWaves)
+        launch_cfg<T_, 2, true>(x, w, y, p, st);
+    else if (waves(2) >= kEnoughWaves || waves(1) < 64)
         launch_cfg<T_, 2, false>(x, w, y, p, st);
+    else
+        launch_cfg<T_, 1, false>(x, w, y, p, st);
     return hipGetLastError();
 }
 
