@@ -40,6 +40,9 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     ap.add_argument("--only", default="", help="time only this pass (fwd|bwi|bww) in the step loop; for profiling")
+    ap.add_argument("--sweep", default="", metavar="FILE.json",
+                    help="also time every configuration (overlap sweep, 14x14 layer fp32/bf16, expanding layer, "
+                         "13-layer stack) pass by pass and write the table to this file")
     return ap.parse_args()
 
 
@@ -53,27 +56,14 @@ def pick_workload(name):
     return table[name]
 
 
-def main():
-    args = parse()
-    if args.gpus != 1:
-        print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
-        sys.exit(2)
-    import numpy as np
-    import torch
-
-    import paper_2101_00745_amd as S
-    import scc_workloads as Wk
-
-    if not torch.cuda.is_available():
-        print("bench.py needs the GPU: there is no CPU path", file=sys.stderr)
-        sys.exit(2)
-    S.load()
-    layer, dtype = pick_workload(args.workload)
+def measure(S, Wk, torch, layer, dtype, steps, warmup, eager=False, only="", whole_step=True):
+    """Times one layer: the whole step (all passes back to back) and each pass on its own.
+    Returns (inputs, dict of figures)."""
     esz = 4 if dtype == torch.float32 else 2
     dev = torch.device("cuda:0")
     x, w, dy = Wk.make_inputs(layer)
     set_bytes = esz * 2 * layer.N * layer.HW * (layer.Cin + layer.Cout)
-    R = max(2, -(-ROTATE_BYTES // set_bytes))
+    R = max(2, min(64, -(-ROTATE_BYTES // set_bytes)))
     sets = []
     for r in range(R):
         xs = torch.from_numpy(x).to(dtype).to(dev)
@@ -99,7 +89,7 @@ def main():
         S.scc_backward_weight(b["x"], b["dy"], layer.cg, layer.co, out=b["dw"], workspace=workspace)
 
     passes = {"fwd": fwd, "bwi": bwi, "bww": bww}
-    step_passes = [args.only] if args.only else ["fwd", "bwi", "bww"]
+    step_passes = [only] if only else ["fwd", "bwi", "bww"]
 
     def step(b):
         for name in step_passes:
@@ -107,14 +97,13 @@ def main():
 
     # ---- one replayable unit = R steps, one per buffer set -------------------------------------
     side = torch.cuda.Stream()
-    graphs = {}
 
     def make_runner(fn):
         """Returns run(k): enqueue k calls of fn over the rotating buffer sets on `side`."""
-        if args.eager:
-            def run(k, start=0):
+        if eager:
+            def run(k):
                 for i in range(k):
-                    fn(sets[(start + i) % R])
+                    fn(sets[i % R])
             return run
         g = torch.cuda.CUDAGraph()
         with torch.cuda.stream(side):
@@ -124,9 +113,8 @@ def main():
             with torch.cuda.graph(g, stream=side):
                 for b in sets:
                     fn(b)
-        graphs[fn] = g
 
-        def run(k, start=0):
+        def run(k):
             full, rest = divmod(k, R)
             for _ in range(full):
                 g.replay()
@@ -149,22 +137,72 @@ def main():
             wall = time.perf_counter() - t0
         return e0.elapsed_time(e1) / k, wall * 1e3 / k      # ms per call: device events, host wall
 
-    # whole hot path
-    K = max(R, (args.steps // R) * R) if not args.eager else args.steps
-    W = args.warmup
-    run_step = make_runner(step)
-    ms_ev, ms_wall = timed(run_step, K, W)
-    ms_step = max(ms_ev, ms_wall)                          # the slower clock is the honest one
+    K = max(R, (steps // R) * R) if not eager else steps
     alg_bytes = {"fwd": Wk.algorithmic_bytes(layer, esz), "bwi": Wk.algorithmic_bytes(layer, esz),
                  "bww": esz * layer.N * layer.HW * (layer.Cin + layer.Cout) + 4 * layer.Cout * layer.L}
-    step_bytes = sum(alg_bytes[p] for p in step_passes)
-    value = step_bytes / (ms_step * 1e-3) / 1e9
+    res = {"K": K, "R": R, "alg_bytes": alg_bytes, "step_passes": step_passes,
+           "step_bytes": sum(alg_bytes[p] for p in step_passes)}
+    if whole_step:
+        ms_ev, ms_wall = timed(make_runner(step), K, warmup)
+        res.update(ms_ev=ms_ev, ms_wall=ms_wall, ms_step=max(ms_ev, ms_wall))   # the slower clock is the honest one
+    # per-pass average durations (events on the launch stream, back-to-back launches)
+    res["per_pass_ms"] = {name: timed(make_runner(passes[name]), K, warmup)[0] for name in step_passes}
+    return (x, w, dy), res
 
-    # per-kernel average durations (events on the launch stream, back-to-back launches)
-    per_pass = {}
-    for name in step_passes:
-        ev, _ = timed(make_runner(passes[name]), K, W)
-        per_pass[name] = ev
+
+def sweep(S, Wk, torch, steps, warmup, path):
+    """Every configuration of the build, each pass timed on its own; written to `path` and to stderr."""
+    cases = [(l, torch.float32) for l in Wk.METRIC_SWEEP] + [(Wk.LATE, torch.float32), (Wk.LATE, torch.bfloat16),
+                                                             (Wk.EXPAND, torch.float32)]
+    cases += [(l, torch.float32) for l in Wk.STACK]
+    rows = []
+    for layer, dtype in cases:
+        esz = 4 if dtype == torch.float32 else 2
+        _, r = measure(S, Wk, torch, layer, dtype, steps, warmup, whole_step=False)
+        us = {k: v * 1e3 for k, v in r["per_pass_ms"].items()}
+        mb, gf = Wk.algorithmic_bytes(layer, esz) / 1e6, Wk.algorithmic_flops(layer) / 1e9
+        # lower bound of one pass: bytes at the HBM peak or flops at the fp32 matrix peak, whichever is longer
+        bound_us = max(mb * 1e6 / (HBM_PEAK_GBS * 1e9), gf * 1e9 / 157.3e12) * 1e6
+        rows.append({"layer": layer.name, "dtype": "f32" if esz == 4 else "bf16", "MB_per_pass": round(mb, 2),
+                     "GFLOP_per_pass": round(gf, 3), "bound_us_per_pass": round(bound_us, 2),
+                     "us": {k: round(v, 2) for k, v in us.items()}, "us_sum": round(sum(us.values()), 2),
+                     "frac_of_bound": round(3 * bound_us / sum(us.values()), 3)})
+        print("%-36s %-4s %7.1f MB %6.2f GF | fwd %7.1f bwi %7.1f bww %7.1f us | bound %5.1f us/pass" %
+              (layer.name, rows[-1]["dtype"], mb, gf, us["fwd"], us["bwi"], us["bww"], bound_us), file=sys.stderr,
+              flush=True)
+    stack = [r for r in rows if r["layer"].startswith("c5_")]
+    summary = {"stack_us_sum": round(sum(r["us_sum"] for r in stack), 1),
+               "stack_bound_us_sum": round(3 * sum(r["bound_us_per_pass"] for r in stack), 1)}
+    os.makedirs(os.path.dirname(path), exist_ok=True)
+    with open(path, "w") as f:
+        json.dump({"rows": rows, "summary": summary}, f, indent=1)
+    print("stack of 13 layers, three passes each: %.1f us (bound %.1f us)" %
+          (summary["stack_us_sum"], summary["stack_bound_us_sum"]), file=sys.stderr, flush=True)
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+
+    import paper_2101_00745_amd as S
+    import scc_workloads as Wk
+
+    if not torch.cuda.is_available():
+        print("bench.py needs the GPU: there is no CPU path", file=sys.stderr)
+        sys.exit(2)
+    S.load()
+    if args.sweep:
+        sweep(S, Wk, torch, min(args.steps, 64), min(args.warmup, 8), args.sweep)
+    layer, dtype = pick_workload(args.workload)
+    (x, w, dy), r = measure(S, Wk, torch, layer, dtype, args.steps, args.warmup, args.eager, args.only)
+    K, R, W = r["K"], r["R"], args.warmup
+    alg_bytes, step_passes, step_bytes = r["alg_bytes"], r["step_passes"], r["step_bytes"]
+    ms_ev, ms_wall, ms_step, per_pass = r["ms_ev"], r["ms_wall"], r["ms_step"], r["per_pass_ms"]
+    value = step_bytes / (ms_step * 1e-3) / 1e9
     dominant = max(per_pass, key=per_pass.get)
     achieved = alg_bytes[dominant] / (per_pass[dominant] * 1e-3) / 1e9
     traffic = MEASURED_TRAFFIC_BYTES.get(args.workload, {}).get(dominant) if dtype == torch.float32 else None
