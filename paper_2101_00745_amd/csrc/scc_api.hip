@@ -129,12 +129,12 @@ int scc_backward_weight(const void* x, const void* dy, void* dw, int N, int Cin,
         return SCC_ERR_WORKSPACE;
     hipStream_t st = (hipStream_t)stream;
     if (dtype == SCC_F32) {
-        if (scc::backward_weight_mfma_eligible(p) && (((uintptr_t)x | (uintptr_t)dy) & 15u) == 0)
+        if (scc::backward_weight_mfma_eligible(p))
             return launch_status(scc::launch_backward_weight_mfma((const float*)x, (const float*)dy, (float*)dw,
                                                                   (float*)workspace, p, st));
         return launch_status(scc::launch_backward_weight_generic((const float*)x, (const float*)dy, (float*)dw, p, st));
     }
-    if (scc::backward_weight_mfma_eligible(p) && (((uintptr_t)x | (uintptr_t)dy) & 7u) == 0)
+    if (scc::backward_weight_mfma_eligible(p))
         return launch_status(scc::launch_backward_weight_mfma((const scc::bf16_t*)x, (const scc::bf16_t*)dy, (float*)dw,
                                                               (float*)workspace, p, st));
     return launch_status(

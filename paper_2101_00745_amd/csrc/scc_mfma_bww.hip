@@ -43,7 +43,7 @@ struct BwwTiling {
     int NPT;      // span positions per wavefront tile / 32
     int NSC;      // span chunks of 32*NPT positions
     int KS;       // K-splits (workgroups per tile and span chunk)
-    int NQ4;      // groups of 4 consecutive columns: N*HW/4
+    int NQ4;      // groups of 4 consecutive columns: ceil(N*HW / 4)
     int per_ks;   // column groups per K-split: ceil(NQ4 / KS)
     int chunk;    // consecutive workgroups of the (K-split, tile) order given to one XCD: ceil(KS * tiles / 8)
 };
@@ -59,7 +59,9 @@ __device__ __forceinline__ void tile_filter(const BwwTiling& T, const Problem& P
 }
 
 // T_ is the storage type of x and dy (float or bf16_t); staged values, products, sums and dw are binary32.
-template <typename T_, int kPosTiles>
+// VEC: H*W is a multiple of 4 and the tensors are aligned to 4 elements, so a lane's 4 consecutive columns
+// lie in one sample and are one vector load; otherwise they are 4 scalar loads with their own addresses.
+template <typename T_, int kPosTiles, bool VEC>
 __global__ __launch_bounds__(kWaves * 64) void backward_weight_mfma32(const T_* __restrict__ x,
                                                                       const T_* __restrict__ dy,
                                                                       float* __restrict__ out, Problem P, BwwTiling T)
@@ -133,16 +135,19 @@ __global__ __launch_bounds__(kWaves * 64) void backward_weight_mfma32(const T_* 
     const int qe = we_ < ks_e ? we_ : ks_e;
     const int nchunk = (qe - qb + 7) / 8;     // chunks of 8 groups = 32 columns
 
-    // this lane's column group in chunk 0, advanced by 8 groups (32 columns) per chunk
-    uint32_t cn, cp;
-    {
-        const uint32_t col = (uint32_t)(qb + lc) * 4u;
-        cn = col / (uint32_t)P.HW;
-        cp = col % (uint32_t)P.HW;
+    // this lane's column group in chunk 0, advanced by 8 groups (32 columns) per chunk; one (sample, pixel)
+    // position for the whole group when it is a vector, one per column otherwise
+    constexpr int NE = VEC ? 1 : 4;
+    uint32_t cp[NE], offA[NE], offB[NE];
+#pragma unroll
+    for (int e = 0; e < NE; ++e) {
+        const uint32_t col = (uint32_t)(qb + lc) * 4u + e;
+        const uint32_t cn = col / (uint32_t)P.HW;
+        cp[e] = col % (uint32_t)P.HW;
+        offA[e] = (cn * (uint32_t)P.Cout * (uint32_t)P.HW + cp[e]) * ES;
+        offB[e] = (cn * (uint32_t)P.Cin * (uint32_t)P.HW + cp[e]) * ES;
     }
     const uint32_t dn = 32u / (uint32_t)P.HW, dp = 32u % (uint32_t)P.HW;
-    uint32_t offA = (cn * (uint32_t)P.Cout * (uint32_t)P.HW + cp) * ES;
-    uint32_t offB = (cn * (uint32_t)P.Cin * (uint32_t)P.HW + cp) * ES;
     const uint32_t stepA = (dn * (uint32_t)P.Cout * (uint32_t)P.HW + dp) * ES;
     const uint32_t stepB = (dn * (uint32_t)P.Cin * (uint32_t)P.HW + dp) * ES;
     const uint32_t wrapA = ((uint32_t)P.Cout - 1u) * plane, wrapB = ((uint32_t)P.Cin - 1u) * plane;
@@ -158,20 +163,38 @@ __global__ __launch_bounds__(kWaves * 64) void backward_weight_mfma32(const T_* 
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[c][v] = 0.f;
 
-    auto load_chunk = [&](ldvec (&r)[kRows / 8], bool& rin) {   // global -> registers, 4 columns of each row
-        rin = qnext < qe;
-        const uint32_t ca = rin ? offA : 0u, cb = rin ? offB : 0u;
+    // global -> registers: 4 columns of each of this lane's rows; `rin` gets one bit per column that exists
+    auto load_chunk = [&](ldvec (&r)[kRows / 8], uint32_t& rin) {
+        const bool gin = qnext < qe;
+        if (VEC) {
+            rin = gin ? 0xfu : 0u;
+            const uint32_t ca = gin ? offA[0] : 0u, cb = gin ? offB[0] : 0u;
 #pragma unroll
-        for (int it = 0; it < kRows / 8; ++it)
-            r[it] = it < 4 ? *(const ldvec*)(ab + (ca + rowoff[it])) : *(const ldvec*)(bb + (cb + rowoff[it]));
+            for (int it = 0; it < kRows / 8; ++it)
+                r[it] = it < 4 ? *(const ldvec*)(ab + (ca + rowoff[it])) : *(const ldvec*)(bb + (cb + rowoff[it]));
+        } else {
+            rin = 0;
+#pragma unroll
+            for (int e = 0; e < NE; ++e) {
+                const bool in = gin && (long long)qnext * 4 + e < P.NQ;
+                rin |= in ? (1u << e) : 0u;
+                const uint32_t ca = in ? offA[e] : 0u, cb = in ? offB[e] : 0u;
+#pragma unroll
+                for (int it = 0; it < kRows / 8; ++it)
+                    r[it][e] = it < 4 ? *(const T_*)(ab + (ca + rowoff[it])) : *(const T_*)(bb + (cb + rowoff[it]));
+            }
+        }
         qnext += 8;
-        cp += dp;
-        const bool wr = cp >= (uint32_t)P.HW;                    // crossed into the next sample
-        cp -= wr ? (uint32_t)P.HW : 0u;
-        offA += stepA + (wr ? wrapA : 0u);
-        offB += stepB + (wr ? wrapB : 0u);
+#pragma unroll
+        for (int e = 0; e < NE; ++e) {
+            cp[e] += dp;
+            const bool wr = cp[e] >= (uint32_t)P.HW;             // crossed into the next sample
+            cp[e] -= wr ? (uint32_t)P.HW : 0u;
+            offA[e] += stepA + (wr ? wrapA : 0u);
+            offB[e] += stepB + (wr ? wrapB : 0u);
+        }
     };
-    auto park_chunk = [&](const ldvec (&r)[kRows / 8], bool rin, bool full) {   // registers -> LDS, widened
+    auto park_chunk = [&](const ldvec (&r)[kRows / 8], uint32_t rin, bool full) {   // registers -> LDS, widened
         if (full) {
 #pragma unroll
             for (int it = 0; it < kRows / 8; ++it) {
@@ -185,7 +208,7 @@ __global__ __launch_bounds__(kWaves * 64) void backward_weight_mfma32(const T_* 
             for (int it = 0; it < kRows / 8; ++it) {
                 f32x4 v;
 #pragma unroll
-                for (int e = 0; e < 4; ++e) v[e] = rin ? to_f32((T_)r[it][e]) : 0.f;
+                for (int e = 0; e < 4; ++e) v[e] = (rin >> e) & 1u ? to_f32((T_)r[it][e]) : 0.f;
                 *(f32x4*)(stage + (8 * it + lr) * kLd + 4 * lc) = v;
             }
         }
@@ -210,17 +233,17 @@ __global__ __launch_bounds__(kWaves * 64) void backward_weight_mfma32(const T_* 
     // 48 KB per wavefront queued the first data arrives ~6 us after issue whatever the wait policy,
     // so a batch of kDepth chunks is waited for as a whole.)
     ldvec r[kDepth][kRows / 8];
-    bool in[kDepth];
+    uint32_t in[kDepth];
 #pragma unroll
     for (int d = 0; d < kDepth; ++d) {
-        in[d] = false;
+        in[d] = 0;
         if (d < nchunk) load_chunk(r[d], in[d]);
     }
     for (int ci = 0; ci < nchunk; ci += kDepth) {
 #pragma unroll
         for (int d = 0; d < kDepth; ++d) {
             if (ci + d < nchunk) {
-                park_chunk(r[d], in[d], qb + 8 * (ci + d + 1) <= qe);
+                park_chunk(r[d], in[d], qb + 8 * (ci + d + 1) <= qe && (long long)(qb + 8 * (ci + d + 1)) * 4 <= P.NQ);
                 if (ci + d + kDepth < nchunk) load_chunk(r[d], in[d]);
                 mma_chunk();
             }
@@ -283,18 +306,18 @@ int pow2_floor(int v)
     return p;
 }
 
-template <typename T_, int NPT>
+template <typename T_, int NPT, bool VEC>
 hipError_t launch_tile(dim3 grid, dim3 block, hipStream_t st, const T_* x, const T_* dy, float* out, const Problem& p,
                        const BwwTiling& t)
 {
     if (lds_bytes_of(NPT) > 64 * 1024) {
         // more than 64 KiB of LDS per workgroup has to be allowed once (per process: the library drives one GPU)
-        static const hipError_t allowed = hipFuncSetAttribute((const void*)backward_weight_mfma32<T_, NPT>,
+        static const hipError_t allowed = hipFuncSetAttribute((const void*)backward_weight_mfma32<T_, NPT, VEC>,
                                                               hipFuncAttributeMaxDynamicSharedMemorySize,
                                                               (int)lds_bytes_of(NPT));
         if (allowed != hipSuccess) return allowed;
     }
-    backward_weight_mfma32<T_, NPT><<<grid, block, lds_bytes_of(NPT), st>>>(x, dy, out, p, t);
+    backward_weight_mfma32<T_, NPT, VEC><<<grid, block, lds_bytes_of(NPT), st>>>(x, dy, out, p, t);
     return hipGetLastError();
 }
 
@@ -319,7 +342,7 @@ BwwTiling make_tiling(const Problem& p)
         }
     }
     t.NSC = (t.U + 32 * t.NPT - 1) / (32 * t.NPT);
-    t.NQ4 = (int)(p.NQ / 4);
+    t.NQ4 = (int)((p.NQ + 3) / 4);   // the last group is partial when N*H*W is not a multiple of 4
     // about one workgroup per CU (one wavefront per SIMD, deep prefetch), at least 32 column groups per wavefront
     const long long tiles = (long long)t.IB * t.MB * t.NSC;
     long long ks = (256 + tiles - 1) / tiles;
@@ -337,7 +360,7 @@ BwwTiling make_tiling(const Problem& p)
 bool backward_weight_mfma_eligible(const Problem& p)
 {
     const long long rows = p.Cin > p.Cout ? p.Cin : p.Cout;
-    return p.HW % 4 == 0 && p.L >= 8 && p.NQ >= 256 && p.Cout >= 8 && p.Cin < 65536 &&
+    return p.L >= 8 && p.NQ >= 256 && p.Cout >= 8 && p.Cin < 65536 &&
            (long long)p.NQ * rows * 4 < (1ll << 32) && (long long)p.Cout * p.L * 4 < (1ll << 31);
 }
 
@@ -356,12 +379,17 @@ hipError_t launch_backward_weight_mfma(const T_* x, const T_* dy, float* dw, flo
     float* out = t.KS > 1 ? workspace : dw;
     const dim3 grid((unsigned)blocks), block(kWaves * 64);
     hipError_t e = hipSuccess;
+    // vector loads of 4 columns need planes whose size is a multiple of 4 and tensors aligned to 4 elements
+    const bool vec = p.HW % 4 == 0 && (((uintptr_t)x | (uintptr_t)dy) & (4 * sizeof(T_) - 1)) == 0;
     if (t.NPT == 1)
-        e = launch_tile<T_, 1>(grid, block, st, x, dy, out, p, t);
+        e = vec ? launch_tile<T_, 1, true>(grid, block, st, x, dy, out, p, t)
+                : launch_tile<T_, 1, false>(grid, block, st, x, dy, out, p, t);
     else if (t.NPT == 2)
-        e = launch_tile<T_, 2>(grid, block, st, x, dy, out, p, t);
+        e = vec ? launch_tile<T_, 2, true>(grid, block, st, x, dy, out, p, t)
+                : launch_tile<T_, 2, false>(grid, block, st, x, dy, out, p, t);
     else
-        e = launch_tile<T_, 3>(grid, block, st, x, dy, out, p, t);
+        e = vec ? launch_tile<T_, 3, true>(grid, block, st, x, dy, out, p, t)
+                : launch_tile<T_, 3, false>(grid, block, st, x, dy, out, p, t);
     if (e != hipSuccess) return e;
     e = hipGetLastError();
     if (e != hipSuccess || t.KS == 1) return e;
