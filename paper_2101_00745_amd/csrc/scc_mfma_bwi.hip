@@ -35,7 +35,9 @@ __device__ __forceinline__ int floor_div(int a, int b)  // b > 0
 }
 
 // T_ is the storage type of dy, w, dx (float or bf16_t); arithmetic is binary32 either way.
-template <typename T_, int CT, int KC, bool VEC>
+// S wavefronts (1, 2 or 4) share one tile, each taking a slice of the (window, filter) slots; their partial
+// tiles are added through LDS in slice order (layers with few columns and many covering filters).
+template <typename T_, int CT, int KC, bool VEC, int S>
 __global__ __launch_bounds__(256) void backward_input_mfma32(const T_* __restrict__ dy, const T_* __restrict__ w,
                                                              T_* __restrict__ dx, Problem P, BwiTiling T)
 {
@@ -50,19 +52,23 @@ __global__ __launch_bounds__(256) void backward_input_mfma32(const T_* __restric
     const int ct = logical / T.FG;
     const int fg = logical % T.FG;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-    const int cb = fg * 4 + wave;
-    if (cb >= T.CB) return;
+    const int cb = fg * (4 / S) + wave / S, split = wave % S;
+    const bool tvalid = cb < T.CB;
+    if (S == 1 && !tvalid) return;              // with S > 1 every wavefront has to reach the barrier
 
     const int lane = threadIdx.x & 63;
     const int f = lane & 31, h = lane >> 5;
     const int c0 = cb * 32;
     const int c = c0 + f;                       // this lane's input channel (A row)
-    const bool cvalid = c < P.Cin;
+    const bool cvalid = tvalid && c < P.Cin;
     // unwrapped window index range: g*m in [c0-L+1, c0+31]
     const int mlo = -floor_div(P.L - 1 - c0, T.b.g);   // ceil((c0-L+1)/g)
     const int M = floor_div(c0 + 31, T.b.g) - mlo + 1;  // window starts this block can see (>= 1)
     // K-steps: each half-wave walks Uh (window, filter) slots; an even number of chunks
     const int Uh = ((M * T.b.F + 1) / 2 + 2 * KC - 1) / (2 * KC) * (2 * KC);
+    const int Us = ((Uh + S - 1) / S + 2 * KC - 1) / (2 * KC) * (2 * KC);   // K-steps of one slice
+    const int t0 = split * Us < Uh ? split * Us : Uh;                         // this wavefront's K-steps [t0, t1)
+    const int t1 = !tvalid ? t0 : (t0 + Us < Uh ? t0 + Us : Uh);
     const char* wb = (const char*)w;
     const char* gb = (const char*)dy;
 
@@ -79,7 +85,7 @@ __global__ __launch_bounds__(256) void backward_input_mfma32(const T_* __restric
     }
 
     // K-slot state of this half-wave: slot u = h*Uh + t  <->  (mm, i) = (u / F, u % F)
-    const int u0 = h * Uh;
+    const int u0 = h * Uh + t0;
     int mm = u0 / T.b.F, i = u0 % T.b.F;
     int mw = (mlo + mm) % T.b.P;                 // window index on the circle
     if (mw < 0) mw += T.b.P;
@@ -134,17 +140,40 @@ __global__ __launch_bounds__(256) void backward_input_mfma32(const T_* __restric
     T_ a0[KC], a1[KC];
     bvec b0[KC], b1[KC];
     uint32_t m0, m1;
-    const int nch = Uh / KC;
-    load_chunk(a0, m0, b0);
-    for (int cix = 0; cix + 2 < nch; cix += 2) {
+    const int nch = (t1 - t0) / KC;
+    if (nch > 0) {
+        load_chunk(a0, m0, b0);
+        for (int cix = 0; cix + 2 < nch; cix += 2) {
+            load_chunk(a1, m1, b1);
+            mma_chunk(a0, m0, b0);
+            load_chunk(a0, m0, b0);
+            mma_chunk(a1, m1, b1);
+        }
         load_chunk(a1, m1, b1);
         mma_chunk(a0, m0, b0);
-        load_chunk(a0, m0, b0);
         mma_chunk(a1, m1, b1);
     }
-    load_chunk(a1, m1, b1);
-    mma_chunk(a0, m0, b0);
-    mma_chunk(a1, m1, b1);
+
+    if constexpr (S > 1) {   // add the slices of each tile, in slice order, into the wavefront that took slice 0
+        __shared__ float red[(S > 1 ? (4 / S) * (S - 1) : 1) * CT * 16 * 64];
+        float* mine = red + ((wave / S) * (S - 1) + (split - 1)) * (CT * 16 * 64) + lane;
+        if (split > 0) {
+#pragma unroll
+            for (int cc = 0; cc < CT; ++cc)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) mine[(cc * 16 + v) * 64] = acc[cc][v];
+        }
+        __syncthreads();
+        if (split > 0 || !tvalid) return;
+#pragma unroll
+        for (int sp = 1; sp < S; ++sp) {
+            const float* other = red + ((wave / S) * (S - 1) + (sp - 1)) * (CT * 16 * 64) + lane;
+#pragma unroll
+            for (int cc = 0; cc < CT; ++cc)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[cc][v] += other[(cc * 16 + v) * 64];
+        }
+    }
 
     // accumulator register v holds tile row 8*(v/4) + 4*h + v%4 (= channel c0 + that), column f
 #pragma unroll
@@ -167,19 +196,36 @@ __global__ __launch_bounds__(256) void backward_input_mfma32(const T_* __restric
     }
 }
 
-template <typename T_, int CT, bool VEC>
-void launch_cfg(const T_* dy, const T_* w, T_* dx, const Problem& p, hipStream_t st)
+template <typename T_, int CT, bool VEC, int S>
+void launch_split(const T_* dy, const T_* w, T_* dx, const Problem& p, hipStream_t st)
 {
     constexpr int KC = 8;
     BwiTiling t;
     t.b = make_band(p);
     t.CB = (p.Cin + 31) / 32;
     const long long nct = (p.NQ + 32 * CT - 1) / (32 * CT);
-    t.FG = (t.CB + 3) / 4;
+    t.FG = (t.CB * S + 3) / 4;
     t.total = (int)(nct * t.FG);
     t.chunk = (t.total + 7) / 8;
     const long long blocks = (long long)8 * t.chunk;
-    backward_input_mfma32<T_, CT, KC, VEC><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(dy, w, dx, p, t);
+    backward_input_mfma32<T_, CT, KC, VEC, S><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(dy, w, dx, p, t);
+}
+
+template <typename T_, int CT, bool VEC>
+void launch_cfg(const T_* dy, const T_* w, T_* dx, const Problem& p, hipStream_t st, long long waves)
+{
+    // share a tile between 2 or 4 wavefronts while there are fewer than two wavefronts per SIMD and each slice
+    // keeps at least 32 K-steps; a block of 32 channels sees about (L+31)/g windows of F filters each
+    const Band b = make_band(p);
+    const long long slots = ((long long)(p.L + 31) / b.g + 1) * b.F;
+    int split = 1;
+    while (split < 4 && waves * split < 2048 && slots / (4 * split) >= 32) split *= 2;
+    if (CT > 1 || split == 1)     // only the narrowest tile is ever short of wavefronts
+        launch_split<T_, CT, VEC, 1>(dy, w, dx, p, st);
+    else if (split == 2)
+        launch_split<T_, CT, VEC, 2>(dy, w, dx, p, st);
+    else
+        launch_split<T_, CT, VEC, 4>(dy, w, dx, p, st);
 }
 
 }  // namespace
@@ -205,13 +251,13 @@ hipError_t launch_backward_input_mfma(const T_* dy, const T_* w, T_* dx, const P
     const uintptr_t addr = (uintptr_t)dy | (uintptr_t)dx;
     auto vec_ok = [&](int ct) { return p.HW % ct == 0 && (addr & (ct * sizeof(T_) - 1)) == 0; };
     if (vec_ok(4) && waves(4) >= kEnoughWaves)
-        launch_cfg<T_, 4, true>(dy, w, dx, p, st);
+        launch_cfg<T_, 4, true>(dy, w, dx, p, st, waves(4));
     else if (vec_ok(2) && waves(2) >= kEnoughWaves)
-        launch_cfg<T_, 2, true>(dy, w, dx, p, st);
-    else if (waves(2) >= kEnoughWaves || waves(1) < 64)
-        launch_cfg<T_, 2, false>(dy, w, dx, p, st);
+        launch_cfg<T_, 2, true>(dy, w, dx, p, st, waves(2));
+    else if (waves(2) >= kEnoughWaves)
+        launch_cfg<T_, 2, false>(dy, w, dx, p, st, waves(2));
     else
-        launch_cfg<T_, 1, false>(dy, w, dx, p, st);
+        launch_cfg<T_, 1, false>(dy, w, dx, p, st, waves(1));
     return hipGetLastError();
 }
 

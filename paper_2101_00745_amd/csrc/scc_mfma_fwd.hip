@@ -26,7 +26,8 @@ struct FwdTiling {
     int TI, TM;    // tile = TM starts x TI filters per start; TI*TM <= 32 (TM is capped by P)
     int IB, MB;    // tiles along i and m
     int Uh;        // K-steps per tile (multiple of the chunk length); each half-wave covers Uh channels
-    int FG;        // workgroups per column tile = ceil(IB*MB / 4)
+    int Us;        // K-steps of one wavefront when S wavefronts share a tile: ceil(Uh / S) rounded to rounds
+    int FG;        // workgroups per column tile = ceil(IB*MB * S / 4)
     int total;     // workgroups with work: column tiles (of 32*CT columns) * FG, filter-tile group fastest
     int chunk;     // consecutive workgroups of that order given to one XCD: ceil(total / 8)
 };
@@ -38,7 +39,9 @@ struct FwdTiling {
 //      one CT*4-byte store per output row); otherwise a lane owns columns f, f+32, ...
 // T    storage type of x, w, y (float or bf16_t); products and sums are binary32 either way: bf16
 //      values are widened in registers and go through the same fp32 matrix instruction
-template <typename T_, int CT, int KC, bool AL4, bool VEC>
+// S    wavefronts sharing one tile (1, 2 or 4), each taking a slice of the contraction; their partial
+//      tiles are added through LDS in slice order.  For layers with few columns and long windows.
+template <typename T_, int CT, int KC, bool AL4, bool VEC, int S>
 __global__ __launch_bounds__(256) void forward_mfma32(const T_* __restrict__ x, const T_* __restrict__ w,
                                                       T_* __restrict__ y, Problem P, FwdTiling T)
 {
@@ -57,9 +60,12 @@ __global__ __launch_bounds__(256) void forward_mfma32(const T_* __restrict__ x, 
     const int ct = logical / T.FG;
     const int fg = logical % T.FG;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-    const int tile = fg * 4 + wave;
-    if (tile >= T.IB * T.MB) return;
+    const int tile = fg * (4 / S) + wave / S, split = wave % S;
+    const bool tvalid = tile < T.IB * T.MB;
+    if (S == 1 && !tvalid) return;                   // with S > 1 every wavefront has to reach the barrier
     const int mb = tile / T.IB, ib = tile % T.IB;
+    const int t0 = split * T.Us;                     // this wavefront's K-steps [t0, t1)
+    const int t1 = !tvalid ? t0 : (t0 + T.Us < T.Uh ? t0 + T.Us : T.Uh);
 
     const int lane = threadIdx.x & 63;
     const int f = lane & 31, h = lane >> 5;
@@ -68,7 +74,7 @@ __global__ __launch_bounds__(256) void forward_mfma32(const T_* __restrict__ x, 
     const int mi = f / T.TI, ii = f % T.TI;
     const int m = mb * T.TM + mi, i = ib * T.TI + ii;
     const int k = (int)(((uint32_t)m * (uint32_t)T.b.inv) % (uint32_t)T.b.P) + T.b.P * i;  // P < 65536
-    const bool fvalid = (mi < T.TM) && (m < T.b.P) && (k < P.Cout);
+    const bool fvalid = tvalid && (mi < T.TM) && (m < T.b.P) && (k < P.Cout);
     const int off = T.b.g * mi;                      // this filter's window starts `off` channels into the span
     const int wrow = (fvalid ? k : 0) * P.L;         // first weight of this lane's filter
     const int lo = T.b.g * mb * T.TM;                // first channel of the span (< Cin)
@@ -89,8 +95,8 @@ __global__ __launch_bounds__(256) void forward_mfma32(const T_* __restrict__ x, 
     }
     const uint32_t plane = (uint32_t)P.HW * ES;                  // bytes between channel planes
     const uint32_t wrap = (uint32_t)P.Cin * plane;               // bytes of one sample's channels
-    uint32_t rowofs = (uint32_t)((lo + h * T.Uh) % P.Cin) * plane;  // plane this half-wave reads next
-    int jj = h * T.Uh - off;                                     // weight index this lane reads next
+    uint32_t rowofs = (uint32_t)((lo + h * T.Uh + t0) % P.Cin) * plane;  // plane this half-wave reads next
+    int jj = h * T.Uh + t0 - off;                                // weight index this lane reads next
 
     f32x16 acc[CT];
 #pragma unroll
@@ -151,13 +157,34 @@ __global__ __launch_bounds__(256) void forward_mfma32(const T_* __restrict__ x, 
     // K loop over rounds of KA = 2*KC steps: one round of A loads, B loads KC steps ahead of the
     // matrix instructions.  Uh is a multiple of KA.
     bvec b0[KC], b1[KC];
-    load_b(b0);
-    for (int t = 0; t < T.Uh; t += KA) {
+    if (t0 < t1) load_b(b0);
+    for (int t = t0; t < t1; t += KA) {
         load_a();
         load_b(b1);
         mma(0, b0);
-        if (t + KA < T.Uh) load_b(b0);
+        if (t + KA < t1) load_b(b0);
         mma(KC, b1);
+    }
+
+    if constexpr (S > 1) {   // add the slices of each tile, in slice order, into the wavefront that took slice 0
+        __shared__ float red[(S > 1 ? (4 / S) * (S - 1) : 1) * CT * 16 * 64];
+        float* mine = red + ((wave / S) * (S - 1) + (split - 1)) * (CT * 16 * 64) + lane;
+        if (split > 0) {
+#pragma unroll
+            for (int c = 0; c < CT; ++c)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) mine[(c * 16 + v) * 64] = acc[c][v];
+        }
+        __syncthreads();
+        if (split > 0 || !tvalid) return;
+#pragma unroll
+        for (int sp = 1; sp < S; ++sp) {
+            const float* other = red + ((wave / S) * (S - 1) + (sp - 1)) * (CT * 16 * 64) + lane;
+#pragma unroll
+            for (int c = 0; c < CT; ++c)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[c][v] += other[(c * 16 + v) * 64];
+        }
     }
 
     // ---- store: register v of the accumulator holds tile row 8*(v/4) + 4*h + v%4, column f ----
@@ -203,25 +230,44 @@ FwdTiling filter_tiling(const Problem& p)
     t.MB = (t.b.P + t.TM - 1) / t.TM;
     const int U = p.L + t.b.g * (t.TM - 1);
     t.Uh = (((U + 1) / 2) + 2 * kKC - 1) / (2 * kKC) * (2 * kKC);
+    t.Us = t.Uh;
     t.FG = (t.IB * t.MB + 3) / 4;
     t.total = t.chunk = 0;
     return t;
 }
 
-template <typename T_, int CT, bool VEC>
-void launch_cfg(const T_* x, const T_* w, T_* y, const Problem& p, hipStream_t st)
+template <typename T_, int CT, bool VEC, int S>
+void launch_split(const T_* x, const T_* w, T_* y, const Problem& p, hipStream_t st)
 {
     constexpr int KC = kKC;
     FwdTiling t = filter_tiling(p);
     const long long nct = (p.NQ + 32 * CT - 1) / (32 * CT);
+    t.Us = ((t.Uh + S - 1) / S + 2 * KC - 1) / (2 * KC) * (2 * KC);
+    t.FG = (t.IB * t.MB * S + 3) / 4;
     t.total = (int)(nct * t.FG);
     t.chunk = (t.total + 7) / 8;
     const long long blocks = (long long)8 * t.chunk;
     const bool al4 = (t.b.g % 4 == 0) && (p.L % 4 == 0);
     if (al4)
-        forward_mfma32<T_, CT, KC, true, VEC><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(x, w, y, p, t);
+        forward_mfma32<T_, CT, KC, true, VEC, S><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(x, w, y, p, t);
     else
-        forward_mfma32<T_, CT, KC, false, VEC><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(x, w, y, p, t);
+        forward_mfma32<T_, CT, KC, false, VEC, S><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(x, w, y, p, t);
+}
+
+template <typename T_, int CT, bool VEC>
+void launch_cfg(const T_* x, const T_* w, T_* y, const Problem& p, hipStream_t st, long long waves)
+{
+    // share a tile between 2 or 4 wavefronts while there are fewer than two wavefronts per SIMD and each
+    // slice of the contraction keeps at least 32 K-steps
+    const FwdTiling t = filter_tiling(p);
+    int split = 1;
+    while (split < 4 && waves * split < 2 * kEnoughWaves && t.Uh / (2 * split) >= 32) split *= 2;
+    if (CT > 1 || split == 1)     // only the narrowest tile is ever short of wavefronts
+        launch_split<T_, CT, VEC, 1>(x, w, y, p, st);
+    else if (split == 2)
+        launch_split<T_, CT, VEC, 2>(x, w, y, p, st);
+    else
+        launch_split<T_, CT, VEC, 4>(x, w, y, p, st);
 }
 
 }  // namespace
@@ -247,13 +293,13 @@ hipError_t launch_forward_mfma(const T_* x, const T_* w, T_* y, const Problem& p
     const uintptr_t addr = (uintptr_t)x | (uintptr_t)y | (uintptr_t)w;
     auto vec_ok = [&](int ct) { return p.HW % ct == 0 && (addr & (ct * sizeof(T_) - 1)) == 0; };
     if (vec_ok(4) && waves(4) >= kEnoughWaves)
-        launch_cfg<T_, 4, true>(x, w, y, p, st);
+        launch_cfg<T_, 4, true>(x, w, y, p, st, waves(4));
     else if (vec_ok(2) && waves(2) >= kEnoughWaves)
-        launch_cfg<T_, 2, true>(x, w, y, p, st);
-    else if (waves(2) >= kEnoughWaves || waves(1) < 64)
-        launch_cfg<T_, 2, false>(x, w, y, p, st);
+        launch_cfg<T_, 2, true>(x, w, y, p, st, waves(2));
+    else if (waves(2) >= kEnoughWaves)
+        launch_cfg<T_, 2, false>(x, w, y, p, st, waves(2));
     else
-        launch_cfg<T_, 1, false>(x, w, y, p, st);
+        launch_cfg<T_, 1, false>(x, w, y, p, st, waves(1));
     return hipGetLastError();
 }
 
