@@ -217,8 +217,15 @@ int pow2_floor(int v)
     return p;
 }
 
-constexpr int kKC = 8;            // K-steps per pipelined chunk of B loads
 constexpr int kEnoughWaves = 1024;  // one wavefront per SIMD of the chip
+
+// K-steps per pipelined chunk of B loads: 8, or 4 when rounding the contraction to rounds of 16 steps would
+// pad it more than rounds of 8 do (banded tiles whose span is not a multiple of 32 channels)
+int chunk_steps(int U)
+{
+    const int half = (U + 1) / 2;
+    return (half + 7) / 8 * 8 < (half + 15) / 16 * 16 ? 4 : 8;
+}
 
 FwdTiling filter_tiling(const Problem& p)
 {
@@ -229,17 +236,17 @@ FwdTiling filter_tiling(const Problem& p)
     t.IB = (t.b.F + t.TI - 1) / t.TI;
     t.MB = (t.b.P + t.TM - 1) / t.TM;
     const int U = p.L + t.b.g * (t.TM - 1);
-    t.Uh = (((U + 1) / 2) + 2 * kKC - 1) / (2 * kKC) * (2 * kKC);
+    const int kc = chunk_steps(U);
+    t.Uh = (((U + 1) / 2) + 2 * kc - 1) / (2 * kc) * (2 * kc);
     t.Us = t.Uh;
     t.FG = (t.IB * t.MB + 3) / 4;
     t.total = t.chunk = 0;
     return t;
 }
 
-template <typename T_, int CT, bool VEC, int S>
-void launch_split(const T_* x, const T_* w, T_* y, const Problem& p, hipStream_t st)
+template <typename T_, int CT, bool VEC, int S, int KC>
+void launch_chunk(const T_* x, const T_* w, T_* y, const Problem& p, hipStream_t st)
 {
-    constexpr int KC = kKC;
     FwdTiling t = filter_tiling(p);
     const long long nct = (p.NQ + 32 * CT - 1) / (32 * CT);
     t.Us = ((t.Uh + S - 1) / S + 2 * KC - 1) / (2 * KC) * (2 * KC);
@@ -252,6 +259,17 @@ void launch_split(const T_* x, const T_* w, T_* y, const Problem& p, hipStream_t
         forward_mfma32<T_, CT, KC, true, VEC, S><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(x, w, y, p, t);
     else
         forward_mfma32<T_, CT, KC, false, VEC, S><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(x, w, y, p, t);
+}
+
+template <typename T_, int CT, bool VEC, int S>
+void launch_split(const T_* x, const T_* w, T_* y, const Problem& p, hipStream_t st)
+{
+    const Band b = make_band(p);
+    const int ti = pow2_floor(b.F < 32 ? b.F : 32), tm = 32 / ti < b.P ? 32 / ti : b.P;
+    if (chunk_steps(p.L + b.g * (tm - 1)) == 4)
+        launch_chunk<T_, CT, VEC, S, 4>(x, w, y, p, st);
+    else
+        launch_chunk<T_, CT, VEC, S, 8>(x, w, y, p, st);
 }
 
 template <typename T_, int CT, bool VEC>
