@@ -155,6 +155,8 @@ def sweep(S, Wk, torch, steps, warmup, path):
     cases = [(l, torch.float32) for l in Wk.METRIC_SWEEP] + [(Wk.LATE, torch.float32), (Wk.LATE, torch.bfloat16),
                                                              (Wk.EXPAND, torch.float32)]
     cases += [(l, torch.float32) for l in Wk.STACK]
+    cases += [(l, torch.float32) for l in Wk.CG_SWEEP] + [(l, torch.float32) for l in Wk.BATCH_SWEEP]
+    cases += [(l, torch.bfloat16) for l in [Wk.METRIC, Wk.EXPAND, Wk.BATCH_SWEEP[0], Wk.BATCH_SWEEP[-1]]]
     rows = []
     for layer, dtype in cases:
         esz = 4 if dtype == torch.float32 else 2

@@ -88,6 +88,14 @@ STACK = [Layer("c5_l%02d_%dto%d_%dx%d" % (i, ci, co_, s, s), 5, N=128, Cin=ci, C
 
 ALL_FULL = METRIC_SWEEP + [LATE, EXPAND] + STACK
 
+# The paper's other sweeps on the metric layer (Section 5.3): the number of channel groups cg in
+# {1, 2, 4, 8} at 50% overlap, and the batch size from inference-sized 16 up to 1024.
+# Seeds: config 6 (layer index = position in the cg sweep) and config 7 (position in the batch sweep).
+CG_SWEEP = [replace(METRIC, name="c6_n128_c256_16x16_cg%d_co50" % cg, config=6, cg=cg, layer=i)
+            for i, cg in enumerate((1, 2, 4, 8))]
+BATCH_SWEEP = [replace(METRIC, name="c7_n%d_c256_16x16_cg4_co50" % n, config=7, N=n, layer=i)
+               for i, n in enumerate((16, 32, 64, 128, 256, 512, 1024))]
+
 
 def algorithmic_bytes(layer, elem_bytes=4):
     """Bytes one pass must move when every tensor crosses HBM exactly once."""

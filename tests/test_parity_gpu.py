@@ -140,6 +140,39 @@ def test_mobilenet_shaped_stack(S, layer):
     check_layer(S, layer, torch.float32)
 
 
+@pytest.mark.parametrize("layer", Wk.CG_SWEEP, ids=lambda l: l.name)
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])
+def test_group_count_sweep(S, layer, dtype):
+    # cg = 1 is a (rotated) pointwise convolution with 256-channel windows; cg = 8 has 32-channel windows
+    check_layer(S, layer, dtype)
+
+
+@pytest.mark.parametrize("layer", Wk.BATCH_SWEEP[:3] + Wk.BATCH_SWEEP[4:5], ids=lambda l: l.name)
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])
+def test_batch_sweep(S, layer, dtype):
+    # inference-sized batches (16, 32, 64) and one above the metric layer's (256), every element compared
+    check_layer(S, layer, dtype)
+
+
+def test_largest_batch_sampled(S):
+    # N = 1024 (268 MB per tensor, the top of the paper's batch sweep): forward and grad-input are
+    # independent per sample, so a few samples are compared one by one; grad-weight sums over every
+    # sample and is compared whole.
+    layer = Wk.BATCH_SWEEP[-1]
+    x, w, dy = Wk.make_inputs(layer)
+    xd, wd, dyd = to_dev(x, torch.float32), to_dev(w, torch.float32), to_dev(dy, torch.float32)
+    y = S.scc_forward(xd, wd, layer.cg, layer.co)
+    dx = S.scc_backward_input(dyd, wd, layer.Cin, layer.cg, layer.co)
+    dw = S.scc_backward_weight(xd, dyd, layer.cg, layer.co)
+    torch.cuda.synchronize()
+    sel = [0, 1, 511, 777, 1023]
+    xs, dys, w64 = x[sel].astype(np.float64), dy[sel].astype(np.float64), w.astype(np.float64)
+    assert rel_err(host(y[sel]), O.forward(xs, w64, layer.cg, layer.co)) <= TOL[torch.float32]
+    assert rel_err(host(dx[sel]), O.backward_input(dys, w64, layer.Cin, layer.cg, layer.co)) <= TOL[torch.float32]
+    ref = O.backward_weight(x.astype(np.float64), dy.astype(np.float64), layer.cg, layer.co)
+    assert rel_err(host(dw), ref) <= TOL[torch.float32]
+
+
 def test_adjoint_identity_on_gpu_outputs(S):
     layer = Wk.METRIC
     x, w, dy = Wk.make_inputs(layer)
