@@ -1,4 +1,5 @@
-// Grad-weight of SCC on the gfx950 matrix cores (fp32 MFMA) with a fixed-order reduction.
+// Grad-weight of SCC on the gfx950 matrix cores with a fixed-order reduction: fp32 MFMA for fp32
+// tensors, bf16 MFMA (exact products, fp32 accumulation) for bf16 tensors.
 //
 // dw[k,j] = sum_{n,p} dy[n,k,p] * x[n,(s_k+j) mod Cin,p]     (the derivative of the forward
 // definition with respect to w; Section 4.2 lists it among the backward work without
@@ -13,6 +14,9 @@
 // them in a private, padded LDS block and reads them back in operand layout.  The global loads
 // of the next 32 columns are in flight while the matrix instructions of the current ones issue.
 //
+// bf16 rows are parked as stored (2 bytes per column); a 16-byte LDS read then is one lane's 8 consecutive
+// K values of v_mfma_f32_32x32x16_bf16, so 32 columns take 2 matrix instructions per tile instead of 16.
+//
 // The columns are split over workgroups (K-split) and again over the 4 wavefronts of a
 // workgroup.  Wavefront partials are summed through LDS in wave order, workgroup partials go to
 // the workspace in the layout of dw and a second kernel sums them in split order: no atomics,
@@ -26,14 +30,25 @@ namespace {
 
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint16_t u16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
 constexpr int kWaves = 4;     // wavefronts per workgroup
-constexpr int kLd = 36;       // floats per staged row: 32 columns + 4 of padding (bank spread, 16-byte aligned)
+constexpr int kLd = 36;       // floats per staged fp32 row: 32 columns + 4 of padding (bank spread, 16-byte aligned)
+constexpr int kRowBytes32 = kLd * 4;   // bytes per staged fp32 row
+constexpr int kRowBytes16 = 80;        // bytes per staged bf16 row: 32 columns (64 bytes) + 16 of padding
 
 // NPT = span positions per wavefront tile / 32 (1, 2 or 3): the tile is 32 filters x 32*NPT positions
 constexpr int rows_of(int npt) { return 32 * (1 + npt); }            // operand rows: 32 of dy, 32*NPT of x
 constexpr int depth_of(int) { return 1; }   // chunks of global loads in flight per wavefront: more only queue up
-constexpr size_t lds_bytes_of(int npt) { return (size_t)kWaves * rows_of(npt) * kLd * 4 + 2 * 32 * 4; }
+constexpr int row_bytes_of(int esz) { return esz == 2 ? kRowBytes16 : kRowBytes32; }
+// staging blocks of the wavefronts, reused for the cross-wavefront sum (whichever is larger), + the row tables
+constexpr size_t region_bytes_of(int npt, int esz)
+{
+    const size_t stage = (size_t)kWaves * rows_of(npt) * row_bytes_of(esz), red = (size_t)kWaves * 32 * 32 * npt * 4;
+    return stage > red ? stage : red;
+}
+constexpr size_t lds_bytes_of(int npt, int esz) { return region_bytes_of(npt, esz) + 2 * 32 * 4; }
 
 struct BwwTiling {
     Band b;
@@ -69,12 +84,12 @@ __global__ __launch_bounds__(kWaves * 64) void backward_weight_mfma32(const T_* 
     typedef T_ ldvec __attribute__((ext_vector_type(4)));   // 4 consecutive columns of one row, as stored
     constexpr uint32_t ES = sizeof(T_);
     constexpr int kRows = rows_of(kPosTiles), kDepth = depth_of(kPosTiles);
+    constexpr int kRowB = row_bytes_of((int)ES);
     // per-wavefront staging blocks, reused after the K loop for the cross-wavefront sum; then the filter
     // and span offset of each tile row (k = -1: no such filter)
     extern __shared__ __attribute__((aligned(16))) float lds[];
-    int* row_k = (int*)(lds + kWaves * kRows * kLd);
+    int* row_k = (int*)((char*)lds + region_bytes_of(kPosTiles, (int)ES));
     int* row_off = row_k + 32;
-    static_assert(kWaves * kRows * kLd >= kWaves * 32 * 32 * kPosTiles, "reduction buffer must fit the staging area");
 
     // workgroup -> (K-split, tile, span chunk), tile fastest.  blockIdx % 8 names the XCD and each XCD takes
     // a contiguous run of that order, so the tiles of one K-split, which read the same dy columns and
@@ -155,7 +170,7 @@ __global__ __launch_bounds__(kWaves * 64) void backward_weight_mfma32(const T_* 
 
     const char* ab = (const char*)dy;
     const char* bb = (const char*)x;
-    float* stage = lds + wave * (kRows * kLd);
+    char* stage = (char*)lds + wave * (kRows * kRowB);
 
     f32x16 acc[kPosTiles];
 #pragma unroll
@@ -194,37 +209,56 @@ __global__ __launch_bounds__(kWaves * 64) void backward_weight_mfma32(const T_* 
             offB[e] += stepB + (wr ? wrapB : 0u);
         }
     };
-    auto park_chunk = [&](const ldvec (&r)[kRows / 8], uint32_t rin, bool full) {   // registers -> LDS, widened
-        if (full) {
+    auto park_chunk = [&](const ldvec (&r)[kRows / 8], uint32_t rin, bool full) {   // registers -> LDS
 #pragma unroll
-            for (int it = 0; it < kRows / 8; ++it) {
+        for (int it = 0; it < kRows / 8; ++it) {
+            char* dst = stage + (8 * it + lr) * kRowB + (int)(4 * ES) * lc;
+            if constexpr (ES == 2) {                             // bf16: as stored; zeros past the range
+                ldvec v = r[it];
+                if (!full) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) v[e] = (rin >> e) & 1u ? r[it][e] : (T_)0;
+                }
+                *(ldvec*)dst = v;
+            } else {                                             // fp32 (or widened): zeros past the range
                 f32x4 v;
+                if (full) {
 #pragma unroll
-                for (int e = 0; e < 4; ++e) v[e] = to_f32((T_)r[it][e]);
-                *(f32x4*)(stage + (8 * it + lr) * kLd + 4 * lc) = v;
-            }
-        } else {                                                 // ragged last chunk: zeros past the range
+                    for (int e = 0; e < 4; ++e) v[e] = to_f32((T_)r[it][e]);
+                } else {
 #pragma unroll
-            for (int it = 0; it < kRows / 8; ++it) {
-                f32x4 v;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) v[e] = (rin >> e) & 1u ? to_f32((T_)r[it][e]) : 0.f;
-                *(f32x4*)(stage + (8 * it + lr) * kLd + 4 * lc) = v;
+                    for (int e = 0; e < 4; ++e) v[e] = (rin >> e) & 1u ? to_f32((T_)r[it][e]) : 0.f;
+                }
+                *(f32x4*)dst = v;
             }
         }
     };
     auto mma_chunk = [&]() {                  // LDS -> operand layout -> matrix cores
+        if constexpr (ES == 2) {
 #pragma unroll
-        for (int s = 0; s < 4; ++s) {         // half-wave h takes 16-byte column 2*s + h
-            const f32x4 av = *(const f32x4*)(stage + f * kLd + 4 * (2 * s + h));
-            f32x4 bv[kPosTiles];
+            for (int s = 0; s < 2; ++s) {     // 16 columns per instruction: half-wave h takes columns 16*s + 8*h .. +7
+                const int cb = 32 * s + 16 * h;
+                const bf16x8 av = __builtin_bit_cast(bf16x8, *(const u16x8*)(stage + f * kRowB + cb));
 #pragma unroll
-            for (int c = 0; c < kPosTiles; ++c) bv[c] = *(const f32x4*)(stage + (32 + 32 * c + f) * kLd + 4 * (2 * s + h));
+                for (int c = 0; c < kPosTiles; ++c) {
+                    const bf16x8 bv = __builtin_bit_cast(bf16x8, *(const u16x8*)(stage + (32 + 32 * c + f) * kRowB + cb));
+                    acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, bv, acc[c], 0, 0, 0);
+                }
+            }
+        } else {
 #pragma unroll
-            for (int e = 0; e < 4; ++e)
+            for (int s = 0; s < 4; ++s) {     // half-wave h takes 16-byte column 2*s + h
+                const f32x4 av = *(const f32x4*)(stage + f * kRowB + 16 * (2 * s + h));
+                f32x4 bv[kPosTiles];
 #pragma unroll
                 for (int c = 0; c < kPosTiles; ++c)
-                    acc[c] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[e], bv[c][e], acc[c], 0, 0, 0);
+                    bv[c] = *(const f32x4*)(stage + (32 + 32 * c + f) * kRowB + 16 * (2 * s + h));
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+#pragma unroll
+                    for (int c = 0; c < kPosTiles; ++c)
+                        acc[c] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[e], bv[c][e], acc[c], 0, 0, 0);
+            }
         }
     };
 
@@ -310,14 +344,15 @@ template <typename T_, int NPT, bool VEC>
 hipError_t launch_tile(dim3 grid, dim3 block, hipStream_t st, const T_* x, const T_* dy, float* out, const Problem& p,
                        const BwwTiling& t)
 {
-    if (lds_bytes_of(NPT) > 64 * 1024) {
+    constexpr size_t kLds = lds_bytes_of(NPT, (int)sizeof(T_));
+    if (kLds > 64 * 1024) {
         // more than 64 KiB of LDS per workgroup has to be allowed once (per process: the library drives one GPU)
         static const hipError_t allowed = hipFuncSetAttribute((const void*)backward_weight_mfma32<T_, NPT, VEC>,
                                                               hipFuncAttributeMaxDynamicSharedMemorySize,
-                                                              (int)lds_bytes_of(NPT));
+                                                              (int)kLds);
         if (allowed != hipSuccess) return allowed;
     }
-    backward_weight_mfma32<T_, NPT, VEC><<<grid, block, lds_bytes_of(NPT), st>>>(x, dy, out, p, t);
+    backward_weight_mfma32<T_, NPT, VEC><<<grid, block, kLds, st>>>(x, dy, out, p, t);
     return hipGetLastError();
 }
 
