@@ -32,12 +32,35 @@ template <> __device__ __forceinline__ bf16_t from_f32<bf16_t>(float v)
     return (bf16_t)(u >> 16);
 }
 
+// One bf16 matrix instruction over K = 2*KC: each lane passes KC bf16 values (packed in pairs, low half
+// first) of its A row and of its B column; lanes 0-31 and 32-63 hold different K values.  KC is 8
+// (v_mfma_f32_32x32x16_bf16) or 4 (v_mfma_f32_32x32x8_bf16_1k).  Accumulation is binary32.
+template <int KC>
+__device__ __forceinline__ float __attribute__((ext_vector_type(16)))
+mfma_bf16(const uint32_t (&a)[KC / 2], const uint32_t (&b)[KC / 2], float __attribute__((ext_vector_type(16))) acc)
+{
+    static_assert(KC == 8 || KC == 4, "a chunk is 8 or 4 K-steps");
+    if constexpr (KC == 8) {
+        typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+        typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+        const u32x4 av = {a[0], a[1], a[2], a[3]}, bv = {b[0], b[1], b[2], b[3]};
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, av), __builtin_bit_cast(bf16x8, bv),
+                                                       acc, 0, 0, 0);
+    } else {
+        typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+        typedef short s16x4 __attribute__((ext_vector_type(4)));
+        const u32x2 av = {a[0], a[1]}, bv = {b[0], b[1]};
+        return __builtin_amdgcn_mfma_f32_32x32x8bf16_1k(__builtin_bit_cast(s16x4, av), __builtin_bit_cast(s16x4, bv), acc,
+                                                        0, 0, 0);
+    }
+}
+
 // Generic (any shape) VALU kernels: scc_generic.hip
 template <typename T> hipError_t launch_forward_generic(const T* x, const T* w, T* y, const Problem& p, hipStream_t st);
 template <typename T> hipError_t launch_backward_input_generic(const T* dy, const T* w, T* dx, const Problem& p, hipStream_t st);
 template <typename T> hipError_t launch_backward_weight_generic(const T* x, const T* dy, float* dw, const Problem& p, hipStream_t st);
 
-// Matrix-core (fp32 MFMA) kernels: scc_mfma_*.hip
+// Matrix-core kernels (fp32 MFMA for fp32 tensors, bf16 MFMA for bf16 tensors): scc_mfma_*.hip
 bool forward_mfma_eligible(const Problem& p);
 template <typename T> hipError_t launch_forward_mfma(const T* x, const T* w, T* y, const Problem& p, hipStream_t st);
 bool backward_input_mfma_eligible(const Problem& p);

@@ -1,4 +1,5 @@
-// Grad-input of SCC on the gfx950 matrix cores (fp32 MFMA), as a per-input-channel gather.
+// Grad-input of SCC on the gfx950 matrix cores (fp32 MFMA for fp32 tensors, bf16 MFMA with fp32 sums for
+// bf16 tensors), as a per-input-channel gather.
 //
 // dx[n,c,p] = sum over filters k whose window covers c of w[k,(c-s_k) mod Cin] * dy[n,k,p]
 // (Section 4.2, input-centric backward: every input-gradient element PULLS from the filters
@@ -127,12 +128,32 @@ __global__ __launch_bounds__(256) void backward_input_mfma32(const T_* __restric
         }
     };
     auto mma_chunk = [&](const T_ (&as)[KC], uint32_t am, const bvec (&bs)[KC]) {
+        if constexpr (ES == 2) {
+            // bf16 storage: the KC slots of a chunk are the K values of ONE bf16 matrix instruction per column
+            // group (which K-slot a value takes does not matter as long as A and B agree); exact products
+            uint32_t ap[KC / 2];
 #pragma unroll
-        for (int s = 0; s < KC; ++s) {
-            const float av = (am >> s) & 1u ? to_f32(as[s]) : 0.f;
+            for (int e = 0; e < KC / 2; ++e) {
+                const uint32_t lo = (am >> (2 * e)) & 1u ? (uint32_t)as[2 * e] : 0u;
+                const uint32_t hi = (am >> (2 * e + 1)) & 1u ? (uint32_t)as[2 * e + 1] : 0u;
+                ap[e] = lo | (hi << 16);
+            }
 #pragma unroll
-            for (int cc = 0; cc < CT; ++cc)
-                acc[cc] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, to_f32((T_)bs[s][cc]), acc[cc], 0, 0, 0);
+            for (int cc = 0; cc < CT; ++cc) {
+                uint32_t bp[KC / 2];
+#pragma unroll
+                for (int e = 0; e < KC / 2; ++e)
+                    bp[e] = (uint32_t)(T_)bs[2 * e][cc] | ((uint32_t)(T_)bs[2 * e + 1][cc] << 16);
+                acc[cc] = mfma_bf16<KC>(ap, bp, acc[cc]);
+            }
+        } else {
+#pragma unroll
+            for (int s = 0; s < KC; ++s) {
+                const float av = (am >> s) & 1u ? to_f32(as[s]) : 0.f;
+#pragma unroll
+                for (int cc = 0; cc < CT; ++cc)
+                    acc[cc] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, to_f32((T_)bs[s][cc]), acc[cc], 0, 0, 0);
+            }
         }
     };
 

@@ -1,4 +1,5 @@
-// Forward SCC on the gfx950 matrix cores (fp32 MFMA, exact fp32 products and sums).
+// Forward SCC on the gfx950 matrix cores: fp32 MFMA for fp32 tensors (exact fp32 products and sums),
+// bf16 MFMA for bf16 tensors (exact products, fp32 sums).
 //
 // y[n,k,p] = sum_j w[k,j] * x[n,(s_k+j) mod Cin,p]   (Section 4.2, output-centric forward)
 // is computed as banded GEMM tiles: a tile of 32 filters (TM adjacent window starts x TI
@@ -145,12 +146,33 @@ __global__ __launch_bounds__(256) void forward_mfma32(const T_* __restrict__ x, 
         }
     };
     auto mma = [&](int s0, const bvec (&bs)[KC]) {
+        if constexpr (ES == 2) {
+            // bf16 storage: the KC steps of a chunk are the K values of ONE bf16 matrix instruction per column
+            // group (a half-wave's KC values side by side in its lanes' registers; which K-slot a value takes
+            // does not matter as long as A and B agree).  Products of bf16 values are exact in binary32.
+            uint32_t ap[KC / 2];
 #pragma unroll
-        for (int s = 0; s < KC; ++s) {
-            const float av = (am >> (s0 + s)) & 1u ? to_f32(a[s0 + s]) : 0.f;
+            for (int e = 0; e < KC / 2; ++e) {
+                const uint32_t lo = (am >> (s0 + 2 * e)) & 1u ? (uint32_t)a[s0 + 2 * e] : 0u;
+                const uint32_t hi = (am >> (s0 + 2 * e + 1)) & 1u ? (uint32_t)a[s0 + 2 * e + 1] : 0u;
+                ap[e] = lo | (hi << 16);
+            }
 #pragma unroll
-            for (int c = 0; c < CT; ++c)
-                acc[c] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, to_f32((T_)bs[s][c]), acc[c], 0, 0, 0);
+            for (int c = 0; c < CT; ++c) {
+                uint32_t bp[KC / 2];
+#pragma unroll
+                for (int e = 0; e < KC / 2; ++e)
+                    bp[e] = (uint32_t)(T_)bs[2 * e][c] | ((uint32_t)(T_)bs[2 * e + 1][c] << 16);
+                acc[c] = mfma_bf16<KC>(ap, bp, acc[c]);
+            }
+        } else {
+#pragma unroll
+            for (int s = 0; s < KC; ++s) {
+                const float av = (am >> (s0 + s)) & 1u ? to_f32(a[s0 + s]) : 0.f;
+#pragma unroll
+                for (int c = 0; c < CT; ++c)
+                    acc[c] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, to_f32((T_)bs[s][c]), acc[c], 0, 0, 0);
+            }
         }
     };
 
