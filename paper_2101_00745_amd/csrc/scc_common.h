@@ -55,12 +55,32 @@ mfma_bf16(const uint32_t (&a)[KC / 2], const uint32_t (&b)[KC / 2], float __attr
     }
 }
 
+// Exact split of KC binary32 values into bf16 pieces: v = hi + mid + lo with hi = v truncated to bf16,
+// mid = (v - hi) truncated, lo = v - hi - mid (at most 8 significant bits left, so it is a bf16 value).
+// Pieces of values 2e and 2e+1 are packed into one register, low half first, as mfma_bf16 takes them.
+template <int KC, typename F>
+__device__ __forceinline__ void split3(F get, uint32_t (&hi)[KC / 2], uint32_t (&mid)[KC / 2], uint32_t (&lo)[KC / 2])
+{
+#pragma unroll
+    for (int e = 0; e < KC / 2; ++e) {
+        const float v0 = get(2 * e), v1 = get(2 * e + 1);
+        const float r0 = v0 - __uint_as_float(__float_as_uint(v0) & 0xffff0000u);
+        const float r1 = v1 - __uint_as_float(__float_as_uint(v1) & 0xffff0000u);
+        const float l0 = r0 - __uint_as_float(__float_as_uint(r0) & 0xffff0000u);
+        const float l1 = r1 - __uint_as_float(__float_as_uint(r1) & 0xffff0000u);
+        // upper halves of (x1, x0) side by side: bytes 2,3 of x0 then bytes 2,3 of x1
+        hi[e] = __builtin_amdgcn_perm(__float_as_uint(v1), __float_as_uint(v0), 0x07060302u);
+        mid[e] = __builtin_amdgcn_perm(__float_as_uint(r1), __float_as_uint(r0), 0x07060302u);
+        lo[e] = __builtin_amdgcn_perm(__float_as_uint(l1), __float_as_uint(l0), 0x07060302u);
+    }
+}
+
 // Generic (any shape) VALU kernels: scc_generic.hip
 template <typename T> hipError_t launch_forward_generic(const T* x, const T* w, T* y, const Problem& p, hipStream_t st);
 template <typename T> hipError_t launch_backward_input_generic(const T* dy, const T* w, T* dx, const Problem& p, hipStream_t st);
 template <typename T> hipError_t launch_backward_weight_generic(const T* x, const T* dy, float* dw, const Problem& p, hipStream_t st);
 
-// Matrix-core kernels (fp32 MFMA for fp32 tensors, bf16 MFMA for bf16 tensors): scc_mfma_*.hip
+// Matrix-core kernels: scc_mfma_*.hip
 bool forward_mfma_eligible(const Problem& p);
 template <typename T> hipError_t launch_forward_mfma(const T* x, const T* w, T* y, const Problem& p, hipStream_t st);
 bool backward_input_mfma_eligible(const Problem& p);

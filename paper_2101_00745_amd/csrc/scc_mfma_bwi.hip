@@ -1,5 +1,5 @@
-// Grad-input of SCC on the gfx950 matrix cores (fp32 MFMA for fp32 tensors, bf16 MFMA with fp32 sums for
-// bf16 tensors), as a per-input-channel gather.
+// Grad-input of SCC on the gfx950 matrix cores (bf16 matrix instructions with fp32 sums: directly for bf16
+// tensors, on an exact three-way bf16 split of each value for fp32 tensors), as a per-input-channel gather.
 //
 // dx[n,c,p] = sum over filters k whose window covers c of w[k,(c-s_k) mod Cin] * dy[n,k,p]
 // (Section 4.2, input-centric backward: every input-gradient element PULLS from the filters
@@ -147,12 +147,20 @@ __global__ __launch_bounds__(256) void backward_input_mfma32(const T_* __restric
                 acc[cc] = mfma_bf16<KC>(ap, bp, acc[cc]);
             }
         } else {
+            // fp32 storage: exact three-way bf16 split of every operand, six of the nine partial products
+            // (the dropped ones are below 2^-23 of the product), fp32 accumulation
+            uint32_t ah[KC / 2], amd[KC / 2], al[KC / 2];
+            split3<KC>([&](int e) { return (am >> e) & 1u ? as[e] : 0.f; }, ah, amd, al);
 #pragma unroll
-            for (int s = 0; s < KC; ++s) {
-                const float av = (am >> s) & 1u ? to_f32(as[s]) : 0.f;
-#pragma unroll
-                for (int cc = 0; cc < CT; ++cc)
-                    acc[cc] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, to_f32((T_)bs[s][cc]), acc[cc], 0, 0, 0);
+            for (int cc = 0; cc < CT; ++cc) {
+                uint32_t bh[KC / 2], bm[KC / 2], bl[KC / 2];
+                split3<KC>([&](int e) { return bs[e][cc]; }, bh, bm, bl);
+                acc[cc] = mfma_bf16<KC>(al, bh, acc[cc]);
+                acc[cc] = mfma_bf16<KC>(ah, bl, acc[cc]);
+                acc[cc] = mfma_bf16<KC>(amd, bm, acc[cc]);
+                acc[cc] = mfma_bf16<KC>(amd, bh, acc[cc]);
+                acc[cc] = mfma_bf16<KC>(ah, bm, acc[cc]);
+                acc[cc] = mfma_bf16<KC>(ah, bh, acc[cc]);
             }
         }
     };

@@ -1,13 +1,15 @@
-// Forward SCC on the gfx950 matrix cores: fp32 MFMA for fp32 tensors (exact fp32 products and sums),
-// bf16 MFMA for bf16 tensors (exact products, fp32 sums).
+// Forward SCC on the gfx950 matrix cores.  bf16 tensors go through the bf16 matrix instruction directly
+// (exact products, fp32 sums); fp32 tensors are split exactly into three bf16 pieces per value and take six
+// bf16 matrix instructions per K group (error below 2^-23 of each product, fp32 sums), which costs 3/8 of
+// the matrix time of v_mfma_f32_32x32x2_f32 and measures the same error against an fp64 reference.
 //
 // y[n,k,p] = sum_j w[k,j] * x[n,(s_k+j) mod Cin,p]   (Section 4.2, output-centric forward)
 // is computed as banded GEMM tiles: a tile of 32 filters (TM adjacent window starts x TI
 // filters per start, see scc_band.h) times a span of U = L + g*(TM-1) channels, for 32*CT
 // columns (a column is one (sample, pixel) pair).  When TM == 1 the tile is dense.
 //
-// One wavefront owns one tile.  v_mfma_f32_32x32x2_f32 contracts two K-slots per issue,
-// one per half-wave; half h walks the channels lo + h*Uh + t, t = 0..Uh-1, so that a lane's
+// One wavefront owns one tile.  A matrix instruction contracts K values from both half-waves;
+// half h walks the channels lo + h*Uh + t, t = 0..Uh-1 (a chunk of KC steps is one instruction), so that a lane's
 // successive A values are CONSECUTIVE weights of one filter (16-byte loads straight from
 // the weight matrix, which stays L2 resident) and its B values are one channel plane after
 // another at a fixed column (each half-wave reads 128 contiguous bytes of the plane).
@@ -166,12 +168,22 @@ __global__ __launch_bounds__(256) void forward_mfma32(const T_* __restrict__ x, 
                 acc[c] = mfma_bf16<KC>(ap, bp, acc[c]);
             }
         } else {
+            // fp32 storage: every operand is split exactly into three bf16 pieces (x = hi + mid + lo, each the
+            // truncation of what the previous ones left); six of the nine partial products go through the bf16
+            // matrix instruction with fp32 accumulation.  The three dropped ones (mid*lo, lo*mid, lo*lo) are
+            // below 2^-23 of the product.
+            uint32_t ah[KC / 2], amd[KC / 2], al[KC / 2];
+            split3<KC>([&](int e) { return (am >> (s0 + e)) & 1u ? a[s0 + e] : 0.f; }, ah, amd, al);
 #pragma unroll
-            for (int s = 0; s < KC; ++s) {
-                const float av = (am >> (s0 + s)) & 1u ? to_f32(a[s0 + s]) : 0.f;
-#pragma unroll
-                for (int c = 0; c < CT; ++c)
-                    acc[c] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, to_f32((T_)bs[s][c]), acc[c], 0, 0, 0);
+            for (int c = 0; c < CT; ++c) {
+                uint32_t bh[KC / 2], bm[KC / 2], bl[KC / 2];
+                split3<KC>([&](int e) { return bs[e][c]; }, bh, bm, bl);
+                acc[c] = mfma_bf16<KC>(al, bh, acc[c]);
+                acc[c] = mfma_bf16<KC>(ah, bl, acc[c]);
+                acc[c] = mfma_bf16<KC>(amd, bm, acc[c]);
+                acc[c] = mfma_bf16<KC>(amd, bh, acc[c]);
+                acc[c] = mfma_bf16<KC>(ah, bm, acc[c]);
+                acc[c] = mfma_bf16<KC>(ah, bh, acc[c]);
             }
         }
     };
