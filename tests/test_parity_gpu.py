@@ -43,6 +43,10 @@ def host(t):
     return t.float().cpu().numpy()
 
 
+def host64(t):
+    return t.double().cpu().numpy()
+
+
 def check_layer(S, layer, dtype=torch.float32, seed_offset=0, passes=("fwd", "bwi", "bww")):
     x, w, dy = Wk.make_inputs(layer, seed_offset)
     xd, wd, dyd = to_dev(x, dtype), to_dev(w, dtype), to_dev(dy, dtype)
@@ -171,6 +175,48 @@ def test_largest_batch_sampled(S):
     assert rel_err(host(dx[sel]), O.backward_input(dys, w64, layer.Cin, layer.cg, layer.co)) <= TOL[torch.float32]
     ref = O.backward_weight(x.astype(np.float64), dy.astype(np.float64), layer.cg, layer.co)
     assert rel_err(host(dw), ref) <= TOL[torch.float32]
+
+
+@pytest.mark.parametrize("xs,ws", [(2.0 ** -90, 2.0 ** 40), (2.0 ** 90, 2.0 ** -40), (2.0 ** -40, 2.0 ** -40), (1e-3, 1e3)],
+                         ids=["tiny_x", "huge_x", "tiny_both", "mixed"])
+def test_fp32_dynamic_range(S, xs, ws):
+    # fp32 operands are split into bf16 pieces on the way to the matrix cores; bf16 keeps the binary32 exponent
+    # range, so scaling the inputs by large powers of two must not change the relative error
+    layer = small("range", 8, 64, 64, 8, 8, 2, 0.5)       # 512 columns: the matrix-core kernels take it
+    x, w, dy = Wk.make_inputs(layer)
+    x, w = (x * np.float32(xs)), (w * np.float32(ws))    # dy stays O(1) so that no gradient leaves the fp32 range
+    xd, wd, dyd = to_dev(x, torch.float32), to_dev(w, torch.float32), to_dev(dy, torch.float32)
+    x64, w64, dy64 = x.astype(np.float64), w.astype(np.float64), dy.astype(np.float64)
+    assert rel_err(host64(S.scc_forward(xd, wd, layer.cg, layer.co)), O.forward(x64, w64, layer.cg, layer.co)) <= 2e-6
+    assert rel_err(host64(S.scc_backward_input(dyd, wd, layer.Cin, layer.cg, layer.co)),
+                   O.backward_input(dy64, w64, layer.Cin, layer.cg, layer.co)) <= 2e-6
+    assert rel_err(host64(S.scc_backward_weight(xd, dyd, layer.cg, layer.co)),
+                   O.backward_weight(x64, dy64, layer.cg, layer.co)) <= 2e-6
+
+
+def test_fp32_per_channel_scales(S):
+    # every channel plane has its own scale (2^-30 .. 2^30) and the weights undo it, so all products of a sum
+    # are of similar size although the operands differ by 18 orders of magnitude: an error in the low-order
+    # pieces of the bf16 split of either operand would show at full size
+    layer = small("scales", 8, 96, 80, 8, 8, 3, 0.4)
+    x, w, dy = Wk.make_inputs(layer)
+    rng = np.random.default_rng(4242)
+    sc = (2.0 ** rng.integers(-30, 31, size=layer.Cin)).astype(np.float32)
+    x = x * sc[None, :, None, None]
+    starts = O.starts(layer.Cin, layer.Cout, layer.cg, layer.co)
+    for k in range(layer.Cout):
+        idx = (starts[k] + np.arange(layer.L)) % layer.Cin
+        w[k] = w[k] / sc[idx]
+    xd, wd = to_dev(x, torch.float32), to_dev(w, torch.float32)
+    ref = O.forward(x.astype(np.float64), w.astype(np.float64), layer.cg, layer.co)
+    assert rel_err(host64(S.scc_forward(xd, wd, layer.cg, layer.co)), ref) <= 2e-6
+
+
+def test_fp32_error_is_at_rounding_level(S):
+    # on the metric layer the error against the fp64 oracle is that of fp32 accumulation (a few 1e-7), far
+    # below the 2e-5 bar: the split loses nothing that fp32 arithmetic would keep
+    errs = check_layer(S, Wk.METRIC)
+    assert max(errs.values()) <= 1e-6, errs
 
 
 def test_adjoint_identity_on_gpu_outputs(S):
