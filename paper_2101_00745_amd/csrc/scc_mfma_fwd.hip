@@ -22,7 +22,8 @@ namespace scc {
 namespace {
 
 typedef float f32x16 __attribute__((ext_vector_type(16)));
-typedef float f32x4u __attribute__((ext_vector_type(4), aligned(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 struct FwdTiling {
     Band b;
@@ -51,7 +52,8 @@ __global__ __launch_bounds__(256) void forward_mfma32(const T_* __restrict__ x, 
     typedef T_ bvec __attribute__((ext_vector_type(CT)));               // CT consecutive columns of one plane
     typedef T_ avec __attribute__((ext_vector_type(4), aligned(sizeof(T_))));  // 4 consecutive weights
     constexpr uint32_t ES = sizeof(T_);
-    constexpr int KA = 2 * KC;  // K-steps per round of A loads: 16 consecutive weights = half a 128-byte line per lane
+    constexpr int KA = 2 * KC;   // K-steps per round: two chunks of B loads
+    constexpr int kAB = 2 * KA;  // K-steps per staged block of A operands: two rounds
 
     // workgroup -> (column tile, filter-tile group).  blockIdx % 8 names the XCD; each XCD takes a
     // contiguous run of the (column tile, group) order, so the groups of a column tile, which re-read
@@ -84,6 +86,94 @@ __global__ __launch_bounds__(256) void forward_mfma32(const T_* __restrict__ x, 
     const char* wb = (const char*)w;
     const char* xb = (const char*)x;
 
+    // ---- A operands: through LDS, once per block of kAB K-steps --------------------------------
+    // Read straight into operand layout, every lane would touch its own cache line (64 lines per load
+    // instruction, as much L1 tag traffic as all the activation loads, and the first thing every wavefront
+    // of the chip asks for).  Instead 8 lanes read one filter's 32 consecutive weights (4 lines per 8 lanes),
+    // the values are cut into their bf16 pieces ONCE (fp32: hi, mid, lo; bf16: as stored), zeros where the
+    // window does not reach or the filter does not exist, and parked in a wavefront-private LDS block:
+    // row (h*32 + f), kParts pieces of kAB bf16 each.  A 16-byte LDS read is then one lane's 8 K values of
+    // one piece.  The wavefront is the only user of its block: no barrier.
+    constexpr int kParts = ES == 2 ? 1 : 3;
+    constexpr int kG = kAB / 4;                      // groups of 4 weights in a full block row (8 or 4)
+    constexpr int kPartB = kAB * 2;                  // bytes of one piece of a row
+    constexpr int kRowB = kParts * kPartB + 16;      // + 16 bytes of padding (bank spread, keeps 16-byte alignment)
+    // a wavefront's block also holds its partial tile when S wavefronts share a tile (see the end of the K loop)
+    constexpr int kBlockB = (S > 1 && CT * 16 * 64 * 4 > 64 * kRowB) ? CT * 16 * 64 * 4 : 64 * kRowB;
+    __shared__ __attribute__((aligned(16))) char a_lds[4 * kBlockB];
+    char* A = a_lds + wave * kBlockB;
+    const int offv = fvalid ? off : (1 << 30);       // rows without a filter: every position is outside
+    avec ga[kG];                                     // raw loaded weights; zeroed per mask bit when committed
+    uint32_t gam = 0;                                // bit 4*it + q: weight q of group `it` is inside the window
+    // position of group `it` of a block of nb steps in the (row, group) grid: full blocks take rows f and
+    // 32+f together (kG lanes per row, 64/kG rows per trip), short ones walk the rows in order
+    auto group_pos = [&](int it, int nb, uint32_t& row, uint32_t& c) {
+        if (nb == kAB) {
+            row = (uint32_t)((it % (kG / 2)) * (64 / kG) + lane / kG + 32 * (it / (kG / 2)));
+            c = (uint32_t)(lane % kG);
+        } else {
+            const uint32_t e = (uint32_t)nb >> 2, idx = (uint32_t)(it * 64 + lane);
+            row = idx / e;
+            c = idx - row * e;
+        }
+    };
+    // global -> registers: the weights of K-steps [tb, tb+nb) of both half-waves (nb a multiple of KA, <= kAB)
+    auto stage_issue = [&](int tb, int nb) {
+        gam = 0;
+#pragma unroll
+        for (int it = 0; it < kG; ++it) {
+            uint32_t row, c;
+            group_pos(it, nb, row, c);
+            const bool act = row < 64u;              // short blocks have fewer groups than lanes * kG
+            const int fr = (int)(row & 31u);
+            const int ro = __shfl(offv, fr, 64), rw = __shfl(wrow, fr, 64);
+            const int j0 = (int)((row >> 5) & 1u) * T.Uh + tb + 4 * (int)c - ro;
+            if (AL4) {
+                const bool in = act && j0 >= 0 && j0 < P.L;
+                ga[it] = *(const avec*)(wb + (uint32_t)(in ? rw + j0 : 0) * ES);
+                gam |= in ? (0xfu << (4 * it)) : 0u;
+            } else {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int j = j0 + q;
+                    const bool in = act && j >= 0 && j < P.L;
+                    ga[it][q] = *(const T_*)(wb + (uint32_t)(in ? rw + j : 0) * ES);
+                    gam |= in ? (1u << (4 * it + q)) : 0u;
+                }
+            }
+        }
+    };
+    // registers -> LDS
+    auto stage_commit = [&](int nb) {
+#pragma unroll
+        for (int it = 0; it < kG; ++it) {
+            uint32_t row, c;
+            group_pos(it, nb, row, c);
+            if (row < 64u) {
+                char* dst = A + row * kRowB + 8 * c;
+                const uint32_t m4 = gam >> (4 * it);
+                if constexpr (ES == 2) {
+                    const uint32_t v0 = (m4 & 1u ? (uint32_t)ga[it][0] : 0u) | ((m4 & 2u ? (uint32_t)ga[it][1] : 0u) << 16);
+                    const uint32_t v1 = (m4 & 4u ? (uint32_t)ga[it][2] : 0u) | ((m4 & 8u ? (uint32_t)ga[it][3] : 0u) << 16);
+                    *(u32x2*)dst = u32x2{v0, v1};
+                } else {
+                    const float v[4] = {m4 & 1u ? ga[it][0] : 0.f, m4 & 2u ? ga[it][1] : 0.f, m4 & 4u ? ga[it][2] : 0.f,
+                                        m4 & 8u ? ga[it][3] : 0.f};
+                    uint32_t hi[2], mid[2], lo3[2];
+                    split3<4>([&](int e) { return v[e]; }, hi, mid, lo3);
+                    *(u32x2*)dst = u32x2{hi[0], hi[1]};
+                    *(u32x2*)(dst + kPartB) = u32x2{mid[0], mid[1]};
+                    *(u32x2*)(dst + 2 * kPartB) = u32x2{lo3[0], lo3[1]};
+                }
+            }
+        }
+    };
+
+    // The first block of weights is requested before anything else is computed or loaded.
+    const int nb0 = t1 - t0 < kAB ? t1 - t0 : kAB;
+    if (t0 < t1) stage_issue(t0, nb0);
+    __builtin_amdgcn_sched_barrier(0);
+
     // ---- B side: this lane's columns (byte offsets from x; the launcher checked they fit 32 bits) ----
     uint32_t xcol[CT], ycol[CT];
     bool live[CT];
@@ -99,7 +189,6 @@ __global__ __launch_bounds__(256) void forward_mfma32(const T_* __restrict__ x, 
     const uint32_t plane = (uint32_t)P.HW * ES;                  // bytes between channel planes
     const uint32_t wrap = (uint32_t)P.Cin * plane;               // bytes of one sample's channels
     uint32_t rowofs = (uint32_t)((lo + h * T.Uh + t0) % P.Cin) * plane;  // plane this half-wave reads next
-    int jj = h * T.Uh + t0 - off;                                // weight index this lane reads next
 
     f32x16 acc[CT];
 #pragma unroll
@@ -107,33 +196,6 @@ __global__ __launch_bounds__(256) void forward_mfma32(const T_* __restrict__ x, 
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[c][v] = 0.f;
 
-    // A operands of KA K-steps.  Loads are branch free: a lane whose weight index falls outside its
-    // filter's window reads a safe address; the value is zeroed when it is consumed (not here, so
-    // that nothing waits on a load right after issuing it).  Each lane reads one whole line.
-    T_ a[KA];
-    uint32_t am;
-    auto load_a = [&]() {
-        am = 0;
-#pragma unroll
-        for (int s4 = 0; s4 < KA; s4 += 4) {
-            if (AL4) {
-                const bool in = fvalid && jj >= 0 && jj < P.L;
-                const avec a4 = *(const avec*)(wb + (uint32_t)(in ? (wrow + jj) : 0) * ES);
-#pragma unroll
-                for (int s = 0; s < 4; ++s) a[s4 + s] = a4[s];
-                am |= in ? (0xfu << s4) : 0u;
-            } else {
-#pragma unroll
-                for (int s = 0; s < 4; ++s) {
-                    const int j = jj + s;
-                    const bool in = fvalid && j >= 0 && j < P.L;
-                    a[s4 + s] = *(const T_*)(wb + (uint32_t)(in ? (wrow + j) : 0) * ES);
-                    am |= in ? (1u << (s4 + s)) : 0u;
-                }
-            }
-            jj += 4;
-        }
-    };
     auto load_b = [&](bvec (&bd)[KC]) {
 #pragma unroll
         for (int s = 0; s < KC; ++s) {
@@ -147,62 +209,81 @@ __global__ __launch_bounds__(256) void forward_mfma32(const T_* __restrict__ x, 
             rowofs = (rowofs == wrap) ? 0u : rowofs;             // cyclic wrap past channel Cin-1
         }
     };
-    auto mma = [&](int s0, const bvec (&bs)[KC]) {
-        if constexpr (ES == 2) {
-            // bf16 storage: the KC steps of a chunk are the K values of ONE bf16 matrix instruction per column
-            // group (a half-wave's KC values side by side in its lanes' registers; which K-slot a value takes
-            // does not matter as long as A and B agree).  Products of bf16 values are exact in binary32.
-            uint32_t ap[KC / 2];
+    // The KC steps of a chunk are the K values of one bf16 matrix instruction per column group and pair of
+    // pieces (a half-wave's KC values side by side in its lanes' registers; which K-slot a value takes does
+    // not matter as long as A and B agree).  bf16 tensors: one instruction, exact products.  fp32 tensors:
+    // B is cut into its three bf16 pieces here, and six of the nine partial products are taken (the dropped
+    // mid*lo, lo*mid, lo*lo are below 2^-23 of the product).  Sums are fp32 either way.
+    auto mma = [&](int tl, const bvec (&bs)[KC]) {   // tl: first K-step of the chunk inside the staged block
+        uint32_t ap[kParts][KC / 2];
 #pragma unroll
-            for (int e = 0; e < KC / 2; ++e) {
-                const uint32_t lo = (am >> (s0 + 2 * e)) & 1u ? (uint32_t)a[s0 + 2 * e] : 0u;
-                const uint32_t hi = (am >> (s0 + 2 * e + 1)) & 1u ? (uint32_t)a[s0 + 2 * e + 1] : 0u;
-                ap[e] = lo | (hi << 16);
+        for (int q = 0; q < kParts; ++q) {
+            const char* src = A + (h * 32 + f) * kRowB + q * kPartB + 2 * tl;
+            if constexpr (KC == 8) {
+                const u32x4 t = *(const u32x4*)src;
+#pragma unroll
+                for (int z = 0; z < 4; ++z) ap[q][z] = t[z];
+            } else {
+                const u32x2 t = *(const u32x2*)src;
+                ap[q][0] = t[0];
+                ap[q][1] = t[1];
             }
+        }
 #pragma unroll
-            for (int c = 0; c < CT; ++c) {
+        for (int c = 0; c < CT; ++c) {
+            if constexpr (ES == 2) {
                 uint32_t bp[KC / 2];
 #pragma unroll
                 for (int e = 0; e < KC / 2; ++e)
                     bp[e] = (uint32_t)(T_)bs[2 * e][c] | ((uint32_t)(T_)bs[2 * e + 1][c] << 16);
-                acc[c] = mfma_bf16<KC>(ap, bp, acc[c]);
-            }
-        } else {
-            // fp32 storage: every operand is split exactly into three bf16 pieces (x = hi + mid + lo, each the
-            // truncation of what the previous ones left); six of the nine partial products go through the bf16
-            // matrix instruction with fp32 accumulation.  The three dropped ones (mid*lo, lo*mid, lo*lo) are
-            // below 2^-23 of the product.
-            uint32_t ah[KC / 2], amd[KC / 2], al[KC / 2];
-            split3<KC>([&](int e) { return (am >> (s0 + e)) & 1u ? a[s0 + e] : 0.f; }, ah, amd, al);
-#pragma unroll
-            for (int c = 0; c < CT; ++c) {
+                acc[c] = mfma_bf16<KC>(ap[0], bp, acc[c]);
+            } else {
                 uint32_t bh[KC / 2], bm[KC / 2], bl[KC / 2];
                 split3<KC>([&](int e) { return bs[e][c]; }, bh, bm, bl);
-                acc[c] = mfma_bf16<KC>(al, bh, acc[c]);
-                acc[c] = mfma_bf16<KC>(ah, bl, acc[c]);
-                acc[c] = mfma_bf16<KC>(amd, bm, acc[c]);
-                acc[c] = mfma_bf16<KC>(amd, bh, acc[c]);
-                acc[c] = mfma_bf16<KC>(ah, bm, acc[c]);
-                acc[c] = mfma_bf16<KC>(ah, bh, acc[c]);
+                acc[c] = mfma_bf16<KC>(ap[2], bh, acc[c]);
+                acc[c] = mfma_bf16<KC>(ap[0], bl, acc[c]);
+                acc[c] = mfma_bf16<KC>(ap[1], bm, acc[c]);
+                acc[c] = mfma_bf16<KC>(ap[1], bh, acc[c]);
+                acc[c] = mfma_bf16<KC>(ap[0], bm, acc[c]);
+                acc[c] = mfma_bf16<KC>(ap[0], bh, acc[c]);
             }
         }
     };
 
-    // K loop over rounds of KA = 2*KC steps: one round of A loads, B loads KC steps ahead of the
-    // matrix instructions.  Uh is a multiple of KA.
+    // K loop over rounds of KA = 2*KC steps (Uh and the slices are multiples of KA; a block is two rounds):
+    // B loads run KC steps ahead of the matrix instructions.  The last round is peeled so that no load in the
+    // loop is conditional: behind a branch that may or may not have issued loads, the wait for an operand
+    // has to assume the fewest loads behind it and so also waits for the refill just requested.
     bvec b0[KC], b1[KC];
-    if (t0 < t1) load_b(b0);
-    for (int t = t0; t < t1; t += KA) {
-        load_a();
+    if (t0 < t1) {
+        load_b(b0);
         load_b(b1);
-        mma(0, b0);
-        if (t + KA < t1) load_b(b0);
-        mma(KC, b1);
+        stage_commit(nb0);
+        const int nr = (t1 - t0) / KA;
+        int tb = t0, tl = 0;                          // block start, offset of the round inside the block
+        for (int r = 0; r + 1 < nr; ++r) {
+            // contractions longer than a block: the next block's weights are requested when a block starts and
+            // parked when its last operand has been read, so their latency hides behind the block's rounds
+            if (tl == 0 && tb + kAB < t1) stage_issue(tb + kAB, t1 - tb - kAB < kAB ? t1 - tb - kAB : kAB);
+            mma(tl, b0);
+            load_b(b0);
+            mma(tl + KC, b1);
+            load_b(b1);
+            tl += KA;
+            if (tl == kAB) {
+                tb += kAB;
+                tl = 0;
+                stage_commit(t1 - tb < kAB ? t1 - tb : kAB);
+            }
+        }
+        mma(tl, b0);
+        mma(tl + KC, b1);
     }
 
-    if constexpr (S > 1) {   // add the slices of each tile, in slice order, into the wavefront that took slice 0
-        __shared__ float red[(S > 1 ? (4 / S) * (S - 1) : 1) * CT * 16 * 64];
-        float* mine = red + ((wave / S) * (S - 1) + (split - 1)) * (CT * 16 * 64) + lane;
+    if constexpr (S > 1) {
+        // add the slices of each tile, in slice order, into the wavefront that took slice 0; a wavefront parks
+        // its partial tile in its own (now idle) weight block
+        float* mine = (float*)A + lane;
         if (split > 0) {
 #pragma unroll
             for (int c = 0; c < CT; ++c)
@@ -213,7 +294,7 @@ __global__ __launch_bounds__(256) void forward_mfma32(const T_* __restrict__ x, 
         if (split > 0 || !tvalid) return;
 #pragma unroll
         for (int sp = 1; sp < S; ++sp) {
-            const float* other = red + ((wave / S) * (S - 1) + (sp - 1)) * (CT * 16 * 64) + lane;
+            const float* other = (const float*)(a_lds + (wave + sp) * kBlockB) + lane;
 #pragma unroll
             for (int c = 0; c < CT; ++c)
 #pragma unroll
@@ -314,12 +395,16 @@ void launch_cfg(const T_* x, const T_* w, T_* y, const Problem& p, hipStream_t s
     const FwdTiling t = filter_tiling(p);
     int split = 1;
     while (split < 4 && waves * split < 2 * kEnoughWaves && t.Uh / (2 * split) >= 32) split *= 2;
-    if (CT > 1 || split == 1)     // only the narrowest tile is ever short of wavefronts
+    if constexpr (CT > 1) {       // only the narrowest tile is ever short of wavefronts
         launch_split<T_, CT, VEC, 1>(x, w, y, p, st);
-    else if (split == 2)
-        launch_split<T_, CT, VEC, 2>(x, w, y, p, st);
-    else
-        launch_split<T_, CT, VEC, 4>(x, w, y, p, st);
+    } else {
+        if (split == 1)
+            launch_split<T_, CT, VEC, 1>(x, w, y, p, st);
+        else if (split == 2)
+            launch_split<T_, CT, VEC, 2>(x, w, y, p, st);
+        else
+            launch_split<T_, CT, VEC, 4>(x, w, y, p, st);
+    }
 }
 
 }  // namespace
