@@ -23,7 +23,12 @@
  *     pixel (h, w) (Section 4.2, forward pass).  Only H*W matters.
  *   - Outputs are overwritten, never accumulated into.  An output must not
  *     alias an input.
- *   - dtype SCC_F32: all tensors are IEEE binary32, arithmetic in binary32.
+ *   - dtype SCC_F32: all tensors are IEEE binary32 and all sums are binary32.
+ *     Products are binary32 products, or (forward and grad-input on the matrix
+ *     cores) six of the nine partial products of an exact three-way bfloat16
+ *     split of both factors, which differ from the binary32 product by less
+ *     than 2^-23 of it.  Inf or NaN inputs may give NaN where binary32
+ *     arithmetic would give Inf.
  *     dtype SCC_BF16: x, w, y, dy, dx are bfloat16 (upper half of a binary32,
  *     results rounded to nearest even), products accumulated in binary32;
  *     dw is written as binary32 in BOTH dtypes.

@@ -41,8 +41,8 @@ struct FwdTiling {
 // AL4  g and L are multiples of 4: groups of four weights are wholly inside or outside a window
 // VEC  H*W is a multiple of CT: a lane owns CT CONSECUTIVE columns (one CT*4-byte load per plane,
 //      one CT*4-byte store per output row); otherwise a lane owns columns f, f+32, ...
-// T    storage type of x, w, y (float or bf16_t); products and sums are binary32 either way: bf16
-//      values are widened in registers and go through the same fp32 matrix instruction
+// T    storage type of x, w, y (float or bf16_t); sums are binary32 either way, products go through the
+//      bf16 matrix instruction (bf16 values as stored, fp32 values as three bf16 pieces each)
 // S    wavefronts sharing one tile (1, 2 or 4), each taking a slice of the contraction; their partial
 //      tiles are added through LDS in slice order.  For layers with few columns and long windows.
 template <typename T_, int CT, int KC, bool AL4, bool VEC, int S>
