@@ -297,6 +297,22 @@ def test_random_sweep_matrix_core_shapes(S):
         check_layer(S, layer, torch.bfloat16 if i % 4 == 3 else torch.float32, seed_offset=100 + i)
 
 
+def test_random_sweep_wide_tiles_long_windows(S):
+    """Thousands of columns (128- and 64-column tiles, one wavefront per tile) and windows of 64-320 channels
+    (several staged weight blocks per contraction, contractions shared by 2 or 4 wavefronts), fp32 and bf16."""
+    rng = np.random.default_rng(7452102)
+    for i in range(12):
+        cg = int(rng.choice([1, 2, 4]))
+        L = int(rng.choice([64, 80, 128, 192, 256, 320]))
+        Cin = cg * L
+        Cout = int(rng.integers(24, 260))
+        H = W = int(rng.choice([4, 7, 8, 14, 16]))
+        N = int(rng.integers(8, 48))
+        co = float(rng.choice([0.0, 0.25, 1 / 3, 0.5, 0.75, 0.9]))
+        layer = small("wide%d" % i, N, Cin, Cout, H, W, cg, co)
+        check_layer(S, layer, torch.bfloat16 if i % 3 == 2 else torch.float32, seed_offset=200 + i)
+
+
 def test_unaligned_tensor_views(S):
     """Tensors that start 4 bytes into an allocation: the 16-byte plane accesses must not be used."""
     layer = small("unaligned", 3, 64, 96, 8, 8, 2, 0.5)
