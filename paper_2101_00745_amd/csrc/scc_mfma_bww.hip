@@ -40,7 +40,6 @@ constexpr int kRowBytes16 = 80;        // bytes per staged bf16 row: 32 columns 
 
 // NPT = span positions per wavefront tile / 32 (1, 2 or 3): the tile is 32 filters x 32*NPT positions
 constexpr int rows_of(int npt) { return 32 * (1 + npt); }            // operand rows: 32 of dy, 32*NPT of x
-constexpr int depth_of(int) { return 1; }   // chunks of global loads in flight per wavefront: more only queue up
 constexpr int row_bytes_of(int esz) { return esz == 2 ? kRowBytes16 : kRowBytes32; }
 // staging blocks of the wavefronts, reused for the cross-wavefront sum (whichever is larger), + the row tables
 constexpr size_t region_bytes_of(int npt, int esz)
@@ -83,7 +82,7 @@ __global__ __launch_bounds__(kWaves * 64) void backward_weight_mfma32(const T_* 
 {
     typedef T_ ldvec __attribute__((ext_vector_type(4)));   // 4 consecutive columns of one row, as stored
     constexpr uint32_t ES = sizeof(T_);
-    constexpr int kRows = rows_of(kPosTiles), kDepth = depth_of(kPosTiles);
+    constexpr int kRows = rows_of(kPosTiles);
     constexpr int kRowB = row_bytes_of((int)ES);
     // per-wavefront staging blocks, reused after the K loop for the cross-wavefront sum; then the filter
     // and span offset of each tile row (k = -1: no such filter)
@@ -262,26 +261,18 @@ __global__ __launch_bounds__(kWaves * 64) void backward_weight_mfma32(const T_* 
         }
     };
 
-    // kDepth chunks of global loads are in flight while the matrix instructions of another issue;
-    // the LDS block is private to the wavefront, so the K loop needs no barrier.  (Measured: with
-    // 48 KB per wavefront queued the first data arrives ~6 us after issue whatever the wait policy,
-    // so a batch of kDepth chunks is waited for as a whole.)
-    ldvec r[kDepth][kRows / 8];
-    uint32_t in[kDepth];
-#pragma unroll
-    for (int d = 0; d < kDepth; ++d) {
-        in[d] = 0;
-        if (d < nchunk) load_chunk(r[d], in[d]);
-    }
-    for (int ci = 0; ci < nchunk; ci += kDepth) {
-#pragma unroll
-        for (int d = 0; d < kDepth; ++d) {
-            if (ci + d < nchunk) {
-                park_chunk(r[d], in[d], qb + 8 * (ci + d + 1) <= qe && (long long)(qb + 8 * (ci + d + 1)) * 4 <= P.NQ);
-                if (ci + d + kDepth < nchunk) load_chunk(r[d], in[d]);
-                mma_chunk();
-            }
-        }
+    // One chunk of global loads is in flight while the matrix instructions of the previous one issue; the
+    // LDS block is private to the wavefront, so the K loop needs no barrier.  (Measured: with four chunks,
+    // 48 KB per wavefront, queued the first data arrives ~6 us after issue whatever the wait policy and the
+    // kernel is 3 us slower: more loads in flight than bandwidth x latency only queue up.  Parking the next
+    // chunk in a second LDS block during the matrix instructions was also slower.)
+    ldvec r[kRows / 8];
+    uint32_t in = 0;
+    if (nchunk > 0) load_chunk(r, in);
+    for (int ci = 0; ci < nchunk; ++ci) {
+        park_chunk(r, in, qb + 8 * (ci + 1) <= qe && (long long)(qb + 8 * (ci + 1)) * 4 <= P.NQ);
+        if (ci + 1 < nchunk) load_chunk(r, in);
+        mma_chunk();
     }
     __syncthreads();                           // everyone is done with the staging blocks
 

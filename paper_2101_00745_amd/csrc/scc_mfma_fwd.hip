@@ -9,11 +9,11 @@
 // columns (a column is one (sample, pixel) pair).  When TM == 1 the tile is dense.
 //
 // One wavefront owns one tile.  A matrix instruction contracts K values from both half-waves;
-// half h walks the channels lo + h*Uh + t, t = 0..Uh-1 (a chunk of KC steps is one instruction), so that a lane's
-// successive A values are CONSECUTIVE weights of one filter (16-byte loads straight from
-// the weight matrix, which stays L2 resident) and its B values are one channel plane after
-// another at a fixed column (each half-wave reads 128 contiguous bytes of the plane).
-// The cyclic wrap is a compare-and-subtract on the channel index; nothing is copied.
+// half h walks the channels lo + h*Uh + t, t = 0..Uh-1 (a chunk of KC steps is one instruction), so that a
+// lane's successive A values are CONSECUTIVE weights of one filter (staged through LDS, see the kernel)
+// and its B values are one channel plane after another at a fixed column (each half-wave reads 32*CT
+// contiguous values of the plane).  The cyclic wrap is a compare-and-subtract on the channel index;
+// nothing is copied.
 #include "scc_band.h"
 #include "scc_common.h"
 
