@@ -31,7 +31,7 @@ struct FwdTiling {
     int IB, MB;    // tiles along i and m
     int Uh;        // K-steps per tile (multiple of the chunk length); each half-wave covers Uh channels
     int Us;        // K-steps of one wavefront when S wavefronts share a tile: ceil(Uh / S) rounded to rounds
-    int FG;        // workgroups per column tile = ceil(IB*MB * S / 4)
+    int FG;        // workgroups per column tile = ceil(IB*MB * S / wavefronts per workgroup)
     int total;     // workgroups with work: column tiles (of 32*CT columns) * FG, filter-tile group fastest
     int chunk;     // consecutive workgroups of that order given to one XCD: ceil(total / 8)
 };
@@ -45,8 +45,13 @@ struct FwdTiling {
 //      bf16 matrix instruction (bf16 values as stored, fp32 values as three bf16 pieces each)
 // S    wavefronts sharing one tile (1, 2 or 4), each taking a slice of the contraction; their partial
 //      tiles are added through LDS in slice order.  For layers with few columns and long windows.
-template <typename T_, int CT, int KC, bool AL4, bool VEC, int S>
-__global__ __launch_bounds__(256) void forward_mfma32(const T_* __restrict__ x, const T_* __restrict__ w,
+// WPB  wavefronts per workgroup: 4, or 8 for grids of two or more wavefronts per SIMD.  With 8 the second
+//      four (one per SIMD, like the first four) start their memory traffic only when the first four have
+//      their weights: every wavefront of such a grid is resident at once, and without the stagger all of
+//      them load, then all multiply, then all store; with it one group's stores and arithmetic overlap
+//      the other's loads (18.5 against 21.0 us at the metric layer; used only where it wins, see launch_chunk).
+template <typename T_, int CT, int KC, bool AL4, bool VEC, int S, int WPB>
+__global__ __launch_bounds__(WPB * 64) void forward_mfma32(const T_* __restrict__ x, const T_* __restrict__ w,
                                                       T_* __restrict__ y, Problem P, FwdTiling T)
 {
     typedef T_ bvec __attribute__((ext_vector_type(CT)));               // CT consecutive columns of one plane
@@ -65,9 +70,18 @@ __global__ __launch_bounds__(256) void forward_mfma32(const T_* __restrict__ x, 
     const int ct = logical / T.FG;
     const int fg = logical % T.FG;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-    const int tile = fg * (4 / S) + wave / S, split = wave % S;
+    const int tile = fg * (WPB / S) + wave / S, split = wave % S;
     const bool tvalid = tile < T.IB * T.MB;
-    if (S == 1 && !tvalid) return;                   // with S > 1 every wavefront has to reach the barrier
+    __shared__ int gate;                             // WPB == 8: leaders (wavefronts 0-3) that have their weights
+    if constexpr (WPB == 8) {
+        if (threadIdx.x == 0) gate = 0;
+        __syncthreads();
+    }
+    if (S == 1 && !tvalid) {                         // with S > 1 every wavefront has to reach the barrier
+        if (WPB == 8 && wave < 4 && (threadIdx.x & 63) == 0)
+            __hip_atomic_fetch_add(&gate, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        return;
+    }
     const int mb = tile / T.IB, ib = tile % T.IB;
     const int t0 = split * T.Us;                     // this wavefront's K-steps [t0, t1)
     const int t1 = !tvalid ? t0 : (t0 + T.Us < T.Uh ? t0 + T.Us : T.Uh);
@@ -100,7 +114,7 @@ __global__ __launch_bounds__(256) void forward_mfma32(const T_* __restrict__ x, 
     constexpr int kRowB = kParts * kPartB + 16;      // + 16 bytes of padding (bank spread, keeps 16-byte alignment)
     // a wavefront's block also holds its partial tile when S wavefronts share a tile (see the end of the K loop)
     constexpr int kBlockB = (S > 1 && CT * 16 * 64 * 4 > 64 * kRowB) ? CT * 16 * 64 * 4 : 64 * kRowB;
-    __shared__ __attribute__((aligned(16))) char a_lds[4 * kBlockB];
+    __shared__ __attribute__((aligned(16))) char a_lds[WPB * kBlockB];
     char* A = a_lds + wave * kBlockB;
     const int offv = fvalid ? off : (1 << 30);       // rows without a filter: every position is outside
     avec ga[kG];                                     // raw loaded weights; zeroed per mask bit when committed
@@ -168,6 +182,16 @@ __global__ __launch_bounds__(256) void forward_mfma32(const T_* __restrict__ x, 
             }
         }
     };
+
+    // Followers wait (bounded: a leader always signals, also one without work) before their first request.
+    if constexpr (WPB == 8) {
+        if (wave >= 4) {
+            for (int spin = 0; spin < (1 << 16); ++spin) {
+                if (__hip_atomic_load(&gate, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) >= 4) break;
+                __builtin_amdgcn_s_sleep(2);
+            }
+        }
+    }
 
     // The first block of weights is requested before anything else is computed or loaded.
     const int nb0 = t1 - t0 < kAB ? t1 - t0 : kAB;
@@ -259,6 +283,8 @@ __global__ __launch_bounds__(256) void forward_mfma32(const T_* __restrict__ x, 
         load_b(b0);
         load_b(b1);
         stage_commit(nb0);
+        if (WPB == 8 && wave < 4 && lane == 0)       // this leader has its weights: followers may start
+            __hip_atomic_fetch_add(&gate, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
         const int nr = (t1 - t0) / KA;
         int tb = t0, tl = 0;                          // block start, offset of the round inside the block
         for (int r = 0; r + 1 < nr; ++r) {
@@ -278,6 +304,8 @@ __global__ __launch_bounds__(256) void forward_mfma32(const T_* __restrict__ x, 
         }
         mma(tl, b0);
         mma(tl + KC, b1);
+    } else if (WPB == 8 && wave < 4 && lane == 0) {
+        __hip_atomic_fetch_add(&gate, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
     }
 
     if constexpr (S > 1) {
@@ -359,21 +387,42 @@ FwdTiling filter_tiling(const Problem& p)
     return t;
 }
 
-template <typename T_, int CT, bool VEC, int S, int KC>
-void launch_chunk(const T_* x, const T_* w, T_* y, const Problem& p, hipStream_t st)
+template <typename T_, int CT, bool VEC, int S, int KC, int WPB>
+void launch_wpb(const T_* x, const T_* w, T_* y, const Problem& p, hipStream_t st)
 {
     FwdTiling t = filter_tiling(p);
     const long long nct = (p.NQ + 32 * CT - 1) / (32 * CT);
     t.Us = ((t.Uh + S - 1) / S + 2 * KC - 1) / (2 * KC) * (2 * KC);
-    t.FG = (t.IB * t.MB * S + 3) / 4;
+    t.FG = (t.IB * t.MB * S + WPB - 1) / WPB;
     t.total = (int)(nct * t.FG);
     t.chunk = (t.total + 7) / 8;
     const long long blocks = (long long)8 * t.chunk;
     const bool al4 = (t.b.g % 4 == 0) && (p.L % 4 == 0);
     if (al4)
-        forward_mfma32<T_, CT, KC, true, VEC, S><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(x, w, y, p, t);
+        forward_mfma32<T_, CT, KC, true, VEC, S, WPB><<<dim3((unsigned)blocks), dim3(WPB * 64), 0, st>>>(x, w, y, p, t);
     else
-        forward_mfma32<T_, CT, KC, false, VEC, S><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(x, w, y, p, t);
+        forward_mfma32<T_, CT, KC, false, VEC, S, WPB><<<dim3((unsigned)blocks), dim3(WPB * 64), 0, st>>>(x, w, y, p, t);
+}
+
+template <typename T_, int CT, bool VEC, int S, int KC>
+void launch_chunk(const T_* x, const T_* w, T_* y, const Problem& p, hipStream_t st)
+{
+    // Workgroups of 8 wavefronts with staggered halves: only for grids that fill the chip exactly once with two
+    // wavefronts per SIMD (all resident together, hence in lockstep), dense fp32 tiles of at least two rounds,
+    // and at most 16 flop per byte.  Measured on other shapes it loses: larger grids run in generations that are
+    // out of phase anyway, bf16 and single-round tiles have too little arithmetic to overlap, and layers with
+    // more arithmetic per byte are slowed by the followers' late start.
+    if constexpr (sizeof(T_) == 4 && CT == 4 && VEC && KC == 8 && S == 1) {
+        const FwdTiling t = filter_tiling(p);
+        const long long nct = (p.NQ + 32 * CT - 1) / (32 * CT), waves = nct * t.IB * t.MB;
+        const bool once = waves >= 2 * kEnoughWaves && waves < 2 * kEnoughWaves + kEnoughWaves / 4;
+        const bool light = (long long)p.Cout * p.L <= 32ll * (p.Cin + p.Cout);
+        if (t.TM == 1 && (t.IB * t.MB) % 8 == 0 && t.Uh >= 32 && once && light) {
+            launch_wpb<T_, CT, VEC, S, KC, 8>(x, w, y, p, st);
+            return;
+        }
+    }
+    launch_wpb<T_, CT, VEC, S, KC, 4>(x, w, y, p, st);
 }
 
 template <typename T_, int CT, bool VEC, int S>
