@@ -38,8 +38,10 @@ __device__ __forceinline__ int floor_div(int a, int b)  // b > 0
 // T_ is the storage type of dy, w, dx (float or bf16_t); arithmetic is binary32 either way.
 // S wavefronts (1, 2 or 4) share one tile, each taking a slice of the (window, filter) slots; their partial
 // tiles are added through LDS in slice order (layers with few columns and many covering filters).
-template <typename T_, int CT, int KC, bool VEC, int S>
-__global__ __launch_bounds__(256) void backward_input_mfma32(const T_* __restrict__ dy, const T_* __restrict__ w,
+// WPB wavefronts per workgroup: 4, or 8 (all channel blocks of a column tile on one CU, sharing its L1) for grids
+// that fill the chip exactly once: see launch_split.
+template <typename T_, int CT, int KC, bool VEC, int S, int WPB>
+__global__ __launch_bounds__(WPB * 64) void backward_input_mfma32(const T_* __restrict__ dy, const T_* __restrict__ w,
                                                              T_* __restrict__ dx, Problem P, BwiTiling T)
 {
     typedef T_ bvec __attribute__((ext_vector_type(CT)));
@@ -53,7 +55,7 @@ __global__ __launch_bounds__(256) void backward_input_mfma32(const T_* __restric
     const int ct = logical / T.FG;
     const int fg = logical % T.FG;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-    const int cb = fg * (4 / S) + wave / S, split = wave % S;
+    const int cb = fg * (WPB / S) + wave / S, split = wave % S;
     const bool tvalid = cb < T.CB;
     if (S == 1 && !tvalid) return;              // with S > 1 every wavefront has to reach the barrier
 
@@ -184,7 +186,7 @@ __global__ __launch_bounds__(256) void backward_input_mfma32(const T_* __restric
     }
 
     if constexpr (S > 1) {   // add the slices of each tile, in slice order, into the wavefront that took slice 0
-        __shared__ float red[(S > 1 ? (4 / S) * (S - 1) : 1) * CT * 16 * 64];
+        __shared__ float red[(S > 1 ? (WPB / S) * (S - 1) : 1) * CT * 16 * 64];
         float* mine = red + ((wave / S) * (S - 1) + (split - 1)) * (CT * 16 * 64) + lane;
         if (split > 0) {
 #pragma unroll
@@ -225,19 +227,38 @@ __global__ __launch_bounds__(256) void backward_input_mfma32(const T_* __restric
     }
 }
 
-template <typename T_, int CT, bool VEC, int S>
-void launch_split(const T_* dy, const T_* w, T_* dx, const Problem& p, hipStream_t st)
+template <typename T_, int CT, bool VEC, int S, int WPB>
+void launch_wpb(const T_* dy, const T_* w, T_* dx, const Problem& p, hipStream_t st)
 {
     constexpr int KC = 8;
     BwiTiling t;
     t.b = make_band(p);
     t.CB = (p.Cin + 31) / 32;
     const long long nct = (p.NQ + 32 * CT - 1) / (32 * CT);
-    t.FG = (t.CB * S + 3) / 4;
+    t.FG = (t.CB * S + WPB - 1) / WPB;
     t.total = (int)(nct * t.FG);
     t.chunk = (t.total + 7) / 8;
     const long long blocks = (long long)8 * t.chunk;
-    backward_input_mfma32<T_, CT, KC, VEC, S><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(dy, w, dx, p, t);
+    backward_input_mfma32<T_, CT, KC, VEC, S, WPB><<<dim3((unsigned)blocks), dim3(WPB * 64), 0, st>>>(dy, w, dx, p, t);
+}
+
+template <typename T_, int CT, bool VEC, int S>
+void launch_split(const T_* dy, const T_* w, T_* dx, const Problem& p, hipStream_t st)
+{
+    // Workgroups of 8 wavefronts (0.6 us faster at the metric layer; delaying half of them, which pays in the
+    // forward, does not here): only for grids that fill the chip exactly once with two wavefronts per SIMD, fp32,
+    // windows that start on multiples of 32 channels, and at most 16 flop per byte, the shapes it was measured on.
+    if constexpr (sizeof(T_) == 4 && CT == 4 && VEC && S == 1) {
+        const Band b = make_band(p);
+        const long long cbs = (p.Cin + 31) / 32, nct = (p.NQ + 32 * CT - 1) / (32 * CT), waves = nct * cbs;
+        const bool once = waves >= 2048 && waves < 2048 + 256;
+        const bool light = (long long)p.Cout * p.L <= 32ll * (p.Cin + p.Cout);
+        if (b.g % 32 == 0 && p.Cin % 32 == 0 && cbs % 8 == 0 && once && light) {
+            launch_wpb<T_, CT, VEC, S, 8>(dy, w, dx, p, st);
+            return;
+        }
+    }
+    launch_wpb<T_, CT, VEC, S, 4>(dy, w, dx, p, st);
 }
 
 template <typename T_, int CT, bool VEC>
