@@ -34,6 +34,7 @@ struct FwdTiling {
     int FG;        // workgroups per column tile = ceil(IB*MB * S / wavefronts per workgroup)
     int total;     // workgroups with work: column tiles (of 32*CT columns) * FG, filter-tile group fastest
     int chunk;     // consecutive workgroups of that order given to one XCD: ceil(total / 8)
+    int stagger;   // ticks of the 100 MHz clock the second half of an 8-wavefront workgroup waits after kernel start
 };
 
 // CT   column groups of 32 per wavefront (the tile is 32 filters x 32*CT columns)
@@ -45,11 +46,12 @@ struct FwdTiling {
 //      bf16 matrix instruction (bf16 values as stored, fp32 values as three bf16 pieces each)
 // S    wavefronts sharing one tile (1, 2 or 4), each taking a slice of the contraction; their partial
 //      tiles are added through LDS in slice order.  For layers with few columns and long windows.
-// WPB  wavefronts per workgroup: 4, or 8 for grids of two or more wavefronts per SIMD.  With 8 the second
-//      four (one per SIMD, like the first four) start their memory traffic only when the first four have
-//      their weights: every wavefront of such a grid is resident at once, and without the stagger all of
-//      them load, then all multiply, then all store; with it one group's stores and arithmetic overlap
-//      the other's loads (18.5 against 21.0 us at the metric layer; used only where it wins, see launch_chunk).
+// WPB  wavefronts per workgroup: 4, or 8 for grids of exactly two wavefronts per SIMD.  With 8 the second
+//      four (one per SIMD, like the first four) issue their first request kStaggerTicks after the kernel
+//      started, about when the first four get their first operands: every wavefront of such a grid is
+//      resident at once, and without the stagger all of them load, then all multiply, then all store; with
+//      it one half's stores and arithmetic overlap the other half's loads (17 against 19-21 us at the metric
+//      layer; used only where it wins, see launch_chunk).
 template <typename T_, int CT, int KC, bool AL4, bool VEC, int S, int WPB>
 __global__ __launch_bounds__(WPB * 64) void forward_mfma32(const T_* __restrict__ x, const T_* __restrict__ w,
                                                       T_* __restrict__ y, Problem P, FwdTiling T)
@@ -63,6 +65,7 @@ __global__ __launch_bounds__(WPB * 64) void forward_mfma32(const T_* __restrict_
     // workgroup -> (column tile, filter-tile group).  blockIdx % 8 names the XCD; each XCD takes a
     // contiguous run of the (column tile, group) order, so the groups of a column tile, which re-read
     // the same channel planes, share one XCD and its L2 whenever there are enough column tiles.
+    const uint64_t t_start = WPB == 8 ? __builtin_amdgcn_s_memrealtime() : 0;   // 100 MHz, independent of core clocks
     const int bid = blockIdx.x;
     const int xcd = bid & 7, slot = bid >> 3;
     const int logical = xcd * T.chunk + slot;
@@ -72,16 +75,7 @@ __global__ __launch_bounds__(WPB * 64) void forward_mfma32(const T_* __restrict_
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int tile = fg * (WPB / S) + wave / S, split = wave % S;
     const bool tvalid = tile < T.IB * T.MB;
-    __shared__ int gate;                             // WPB == 8: leaders (wavefronts 0-3) that have their weights
-    if constexpr (WPB == 8) {
-        if (threadIdx.x == 0) gate = 0;
-        __syncthreads();
-    }
-    if (S == 1 && !tvalid) {                         // with S > 1 every wavefront has to reach the barrier
-        if (WPB == 8 && wave < 4 && (threadIdx.x & 63) == 0)
-            __hip_atomic_fetch_add(&gate, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-        return;
-    }
+    if (S == 1 && !tvalid) return;                   // with S > 1 every wavefront has to reach the barrier
     const int mb = tile / T.IB, ib = tile % T.IB;
     const int t0 = split * T.Us;                     // this wavefront's K-steps [t0, t1)
     const int t1 = !tvalid ? t0 : (t0 + T.Us < T.Uh ? t0 + T.Us : T.Uh);
@@ -183,14 +177,10 @@ __global__ __launch_bounds__(WPB * 64) void forward_mfma32(const T_* __restrict_
         }
     };
 
-    // Followers wait (bounded: a leader always signals, also one without work) before their first request.
+    // The second half of the workgroup holds its first request back (the clock runs on: the wait always ends).
     if constexpr (WPB == 8) {
-        if (wave >= 4) {
-            for (int spin = 0; spin < (1 << 16); ++spin) {
-                if (__hip_atomic_load(&gate, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) >= 4) break;
-                __builtin_amdgcn_s_sleep(2);
-            }
-        }
+        if (wave >= 4)
+            while (__builtin_amdgcn_s_memrealtime() - t_start < (uint64_t)T.stagger) __builtin_amdgcn_s_sleep(4);
     }
 
     // The first block of weights is requested before anything else is computed or loaded.
@@ -283,8 +273,6 @@ __global__ __launch_bounds__(WPB * 64) void forward_mfma32(const T_* __restrict_
         load_b(b0);
         load_b(b1);
         stage_commit(nb0);
-        if (WPB == 8 && wave < 4 && lane == 0)       // this leader has its weights: followers may start
-            __hip_atomic_fetch_add(&gate, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
         const int nr = (t1 - t0) / KA;
         int tb = t0, tl = 0;                          // block start, offset of the round inside the block
         for (int r = 0; r + 1 < nr; ++r) {
@@ -304,8 +292,6 @@ __global__ __launch_bounds__(WPB * 64) void forward_mfma32(const T_* __restrict_
         }
         mma(tl, b0);
         mma(tl + KC, b1);
-    } else if (WPB == 8 && wave < 4 && lane == 0) {
-        __hip_atomic_fetch_add(&gate, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
     }
 
     if constexpr (S > 1) {
@@ -361,6 +347,7 @@ int pow2_floor(int v)
 }
 
 constexpr int kEnoughWaves = 1024;  // one wavefront per SIMD of the chip
+constexpr int kStaggerTicks = 250;  // 2.5 us: measured on grids of 2048 wavefronts, 2.3 and 2.8 us gain 2 us, 1.8 us nothing
 
 // K-steps per pipelined chunk of B loads: 8, or 4 when rounding the contraction to rounds of 16 steps would
 // pad it more than rounds of 8 do (banded tiles whose span is not a multiple of 32 channels)
@@ -384,6 +371,7 @@ FwdTiling filter_tiling(const Problem& p)
     t.Us = t.Uh;
     t.FG = (t.IB * t.MB + 3) / 4;
     t.total = t.chunk = 0;
+    t.stagger = kStaggerTicks;
     return t;
 }
 
