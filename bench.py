@@ -22,8 +22,8 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 # HBM bytes per launch of each pass on the metric layer, from two rocprofv3 --pmc runs (FETCH_SIZE scaled by
 # 1.9993, WRITE_SIZE by 1.0; both factors from a plain 64 MiB device copy): profiles/scc_metric_layer_kernels.md
-MEASURED_TRAFFIC_BYTES = {"metric": {"fwd": int((16805.8 * 1.9993 + 32792.8) * 1024),
-                                     "bwi": int((16785.9 * 1.9993 + 32840.6) * 1024),
+MEASURED_TRAFFIC_BYTES = {"metric": {"fwd": int((16783.3 * 1.9993 + 32782.4) * 1024),
+                                     "bwi": int((16785.9 * 1.9993 + 32801.0) * 1024),
                                      "bww": int(((32819.0 + 1038.0) * 1.9993 + 2048.0 + 64.0) * 1024)}}
 KERNELS = {"fwd": ["forward_mfma32"], "bwi": ["backward_input_mfma32"],
            "bww": ["backward_weight_mfma32", "backward_weight_reduce"]}
