@@ -158,6 +158,14 @@ def test_batch_sweep(S, layer, dtype):
     check_layer(S, layer, dtype)
 
 
+def test_chip_filling_grid_with_ragged_tail(S):
+    # 258 column tiles x 8 filter tiles = 2064 wavefronts: the forward and grad-input launch workgroups of 8
+    # wavefronts here (the forward with its second half delayed), with 14x14 planes and a last column tile
+    # that is only a quarter full
+    check_layer(S, small("fills_chip", 168, 256, 256, 14, 14, 4, 0.5))
+    check_layer(S, small("fills_chip_co0", 168, 256, 256, 14, 14, 4, 0.0))
+
+
 def test_largest_batch_sampled(S):
     # N = 1024 (268 MB per tensor, the top of the paper's batch sweep): forward and grad-input are
     # independent per sample, so a few samples are compared one by one; grad-weight sums over every
