@@ -177,10 +177,12 @@ __global__ __launch_bounds__(WPB * 64) void forward_mfma32(const T_* __restrict_
         }
     };
 
-    // The second half of the workgroup holds its first request back (the clock runs on: the wait always ends).
+    // The second half of the workgroup holds its first request back.  The clock runs on, so the wait ends; the
+    // poll count bounds it anyway (64 polls of 256+ cycles each are well beyond the delay).
     if constexpr (WPB == 8) {
         if (wave >= 4)
-            while (__builtin_amdgcn_s_memrealtime() - t_start < (uint64_t)T.stagger) __builtin_amdgcn_s_sleep(4);
+            for (int poll = 0; poll < 64 && __builtin_amdgcn_s_memrealtime() - t_start < (uint64_t)T.stagger; ++poll)
+                __builtin_amdgcn_s_sleep(4);
     }
 
     // The first block of weights is requested before anything else is computed or loaded.
