@@ -9,10 +9,11 @@ INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 LIB = os.path.join(HERE, "libscc_hip.so")
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared", "-fno-gpu-rdc",
-         # packed fp32 VALU forms are kept out of the generated code on purpose
-         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-         "-Wno-unused-command-line-argument", "-Wno-unknown-warning-option"]
+COMPILE_FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-fno-gpu-rdc",
+                 # packed fp32 VALU forms are kept out of the generated code on purpose
+                 "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+                 "-Wno-unused-command-line-argument", "-Wno-unknown-warning-option"]
+LINK_FLAGS = ["--offload-arch=gfx950", "-fPIC", "-shared", "-fno-gpu-rdc", "-Wno-unused-command-line-argument"]
 
 
 def sources():
@@ -27,12 +28,7 @@ def stale():
     return any(os.path.getmtime(f) > t for f in deps)
 
 
-def build(force=True, verbose=False):
-    """Build libscc_hip.so.  With force=False, only when a source is newer than the library."""
-    if not force and not stale():
-        return LIB
-    tmp = LIB + ".tmp.%d" % os.getpid()
-    cmd = [HIPCC] + FLAGS + ["-I", INCLUDE, "-I", CSRC, "-o", tmp] + sources()
+def _run(cmd, verbose):
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
@@ -40,7 +36,33 @@ def build(force=True, verbose=False):
         raise RuntimeError("hipcc failed:\n" + res.stdout)
     if verbose and res.stdout.strip():
         print(res.stdout)
-    os.replace(tmp, LIB)
+
+
+def build(force=True, verbose=False):
+    """Build libscc_hip.so.  With force=False, only when a source is newer than the library.
+    The translation units are compiled side by side (objects in a scratch directory), then linked."""
+    if not force and not stale():
+        return LIB
+    import concurrent.futures
+    import shutil
+    import tempfile
+    work = tempfile.mkdtemp(prefix="scc_build_")
+    try:
+        objs = []
+        with concurrent.futures.ThreadPoolExecutor(max_workers=min(8, len(sources()))) as pool:
+            jobs = []
+            for src in sources():
+                obj = os.path.join(work, os.path.basename(src) + ".o")
+                objs.append(obj)
+                jobs.append(pool.submit(_run, [HIPCC] + COMPILE_FLAGS + ["-I", INCLUDE, "-I", CSRC, "-c", src, "-o", obj],
+                                        verbose))
+            for j in jobs:
+                j.result()
+        tmp = LIB + ".tmp.%d" % os.getpid()
+        _run([HIPCC] + LINK_FLAGS + ["-o", tmp] + objs, verbose)
+        os.replace(tmp, LIB)
+    finally:
+        shutil.rmtree(work, ignore_errors=True)
     return LIB
 
 
