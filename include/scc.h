@@ -15,7 +15,8 @@
  * Conventions shared by every entry point
  *   - Every tensor pointer is a DEVICE pointer owned by the caller.  The library
  *     allocates nothing, keeps no state between calls and never frees or
- *     modifies an input.
+ *     modifies an input.  (scc_backward_weight_static alone uses a buffer the
+ *     library holds itself; see there.)
  *   - Tensors are dense, row-major:  x, dx : [N][Cin][H][W]
  *                                    y, dy : [N][Cout][H][W]
  *                                    w, dw : [Cout][L]
@@ -57,8 +58,12 @@ typedef enum {
     SCC_ERR_OVERLAP = -3,   /* co is not finite or lies outside [0, 1] */
     SCC_ERR_DTYPE = -4,     /* dtype is neither SCC_F32 nor SCC_BF16 */
     SCC_ERR_WORKSPACE = -5, /* workspace missing, misaligned or smaller than the query says */
-    SCC_ERR_LAUNCH = -6     /* the HIP runtime refused a launch (hipGetLastError != hipSuccess) */
+    SCC_ERR_LAUNCH = -6,    /* the HIP runtime refused a launch (hipGetLastError != hipSuccess) */
+    SCC_ERR_SCRATCH = -7    /* scc_backward_weight_static: the problem needs more than SCC_STATIC_SCRATCH_BYTES */
 } scc_status;
+
+/* Size of the device buffer the library itself holds, per GPU, for scc_backward_weight_static. */
+#define SCC_STATIC_SCRATCH_BYTES (8u << 20)
 
 /*
  * Window arithmetic of Algorithm 1, host only (no GPU call).
@@ -111,6 +116,25 @@ size_t scc_backward_weight_workspace_bytes(int N, int Cin, int Cout, int H, int 
 int scc_backward_weight(const void* x, const void* dy, void* dw,
                         int N, int Cin, int Cout, int H, int W, int cg, double co,
                         scc_dtype dtype, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * scc_backward_weight for callers that cannot allocate device memory or hand over a workspace:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, kernels, arithmetic and summation order as scc_backward_weight (results are bitwise
+ * equal), but the scratch is a buffer of SCC_STATIC_SCRATCH_BYTES that the library holds in
+ * device memory on every GPU it runs on, from load until the process ends.  The call allocates
+ * and frees nothing; its first use on a device looks the buffer's address up once (do that
+ * before starting a capture), later calls only enqueue kernels.
+ * Errors: those of scc_backward_weight, and SCC_ERR_SCRATCH when the problem needs more scratch
+ * than the buffer holds (then scc_backward_weight_workspace_bytes(...) > SCC_STATIC_SCRATCH_BYTES;
+ * decided on the host, nothing is launched).
+ * All calls on one GPU share that GPU's buffer: two calls that may run at the same time there
+ * (different streams, or different host threads on different streams) race on it.  Calls ordered
+ * on one stream are safe; nothing in the buffer needs to survive or be cleared between calls.
+ */
+int scc_backward_weight_static(const void* x, const void* dy, void* dw,
+                               int N, int Cin, int Cout, int H, int W, int cg, double co,
+                               scc_dtype dtype, void* stream);
 
 /* Static, human-readable name of a status code (never NULL). */
 const char* scc_status_string(int status);

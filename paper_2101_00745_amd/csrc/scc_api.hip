@@ -5,6 +5,12 @@
 
 #include <cmath>
 #include <limits>
+#include <mutex>
+
+// Scratch of scc_backward_weight_static: the K-split partials of grad-weight live here instead of in a
+// caller-supplied workspace.  One copy per GPU, held until the process ends.  In host code the name is only a
+// handle for hipGetSymbolAddress; the device address it resolves to is what the kernels get.
+static __device__ __align__(256) unsigned char scratch[SCC_STATIC_SCRATCH_BYTES];
 
 namespace {
 
@@ -50,6 +56,26 @@ int make_problem(int N, int Cin, int Cout, int H, int W, int cg, double co, Prob
 bool dtype_ok(scc_dtype d) { return d == SCC_F32 || d == SCC_BF16; }
 
 int launch_status(hipError_t e) { return e == hipSuccess ? SCC_OK : SCC_ERR_LAUNCH; }
+
+// Device address of `scratch` on the current device, resolved once per device (each GPU holds its own copy
+// of the array at its own address).
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void* g_scratch_ptr[kMaxDevices];
+
+int scratch_of_current_device(void** out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return SCC_ERR_LAUNCH;
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        if (hipGetSymbolAddress((void**)&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return SCC_ERR_LAUNCH;
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return SCC_OK;
+}
 
 }  // namespace
 
@@ -141,6 +167,24 @@ int scc_backward_weight(const void* x, const void* dy, void* dw, int N, int Cin,
         scc::launch_backward_weight_generic((const scc::bf16_t*)x, (const scc::bf16_t*)dy, (float*)dw, p, st));
 }
 
+int scc_backward_weight_static(const void* x, const void* dy, void* dw, int N, int Cin, int Cout, int H, int W, int cg,
+                               double co, scc_dtype dtype, void* stream)
+{
+    if (!x || !dy || !dw) return SCC_ERR_NULL;
+    Problem p;
+    const int rc = make_problem(N, Cin, Cout, H, W, cg, co, &p);
+    if (rc != SCC_OK) return rc;
+    if (!dtype_ok(dtype)) return SCC_ERR_DTYPE;
+    const size_t need = scc_backward_weight_workspace_bytes(N, Cin, Cout, H, W, cg, co, dtype);
+    if (need > (size_t)SCC_STATIC_SCRATCH_BYTES) return SCC_ERR_SCRATCH;
+    void* ptr = nullptr;
+    if (need > 0) {
+        const int sc = scratch_of_current_device(&ptr);
+        if (sc != SCC_OK) return sc;
+    }
+    return scc_backward_weight(x, dy, dw, N, Cin, Cout, H, W, cg, co, dtype, ptr, need, stream);
+}
+
 const char* scc_status_string(int status)
 {
     switch (status) {
@@ -151,6 +195,8 @@ const char* scc_status_string(int status)
         case SCC_ERR_DTYPE: return "SCC_ERR_DTYPE: dtype must be SCC_F32 or SCC_BF16";
         case SCC_ERR_WORKSPACE: return "SCC_ERR_WORKSPACE: workspace missing, misaligned or too small";
         case SCC_ERR_LAUNCH: return "SCC_ERR_LAUNCH: the HIP runtime refused the kernel launch";
+        case SCC_ERR_SCRATCH:
+            return "SCC_ERR_SCRATCH: the problem needs more scratch than the library's static buffer holds";
         default: return "unknown scc status";
     }
 }

@@ -15,7 +15,9 @@ LIB_PATH = os.path.join(_HERE, "libscc_hip.so")
 
 SCC_F32, SCC_BF16 = 0, 1
 SYMBOLS = ("scc_window_params", "scc_forward", "scc_backward_input",
-           "scc_backward_weight_workspace_bytes", "scc_backward_weight", "scc_status_string")
+           "scc_backward_weight_workspace_bytes", "scc_backward_weight", "scc_backward_weight_static",
+           "scc_status_string")
+STATIC_SCRATCH_BYTES = 8 << 20    # SCC_STATIC_SCRATCH_BYTES of include/scc.h
 
 _lib = None
 
@@ -48,6 +50,8 @@ def load():
     lib.scc_backward_weight_workspace_bytes.restype = c_sz
     lib.scc_backward_weight.argtypes = [c_vp, c_vp, c_vp] + shape + [c_vp, c_sz, c_vp]
     lib.scc_backward_weight.restype = c_int
+    lib.scc_backward_weight_static.argtypes = [c_vp, c_vp, c_vp] + shape + [c_vp]
+    lib.scc_backward_weight_static.restype = c_int
     lib.scc_status_string.argtypes = [c_int]
     lib.scc_status_string.restype = ctypes.c_char_p
     _lib = lib
@@ -155,3 +159,20 @@ def scc_backward_weight(x, dy, cg, co, out=None, workspace=None):
         _check(load().scc_backward_weight(x.data_ptr(), dy.data_ptr(), dw.data_ptr(), N, Cin, Cout, H, W, cg,
                                           float(co), code, ws_ptr, ws_len, _stream(dev)))
     return dw
+
+
+def scc_backward_weight_static(x, dy, cg, co, out):
+    """scc_backward_weight on the library's own static scratch: the call itself allocates nothing, so the
+    caller passes the output tensor ``out`` (float32 [Cout, Cin//cg])."""
+    dev = _dev(x, dy, out)
+    N, Cin, H, W = x.shape
+    Cout = dy.shape[1]
+    if dy.dtype != x.dtype or dy.shape != (N, Cout, H, W):
+        raise ValueError("dy must be [N,Cout,H,W] with the dtype of x")
+    L = Cin // cg if cg >= 1 and Cin % cg == 0 else 1
+    if out.shape != (Cout, L) or out.dtype != torch.float32:
+        raise ValueError("out must be float32 [Cout, Cin//cg]")
+    with torch.cuda.device(dev):
+        _check(load().scc_backward_weight_static(x.data_ptr(), dy.data_ptr(), out.data_ptr(), N, Cin, Cout, H, W, cg,
+                                                 float(co), _dtype_code(x), _stream(dev)))
+    return out
