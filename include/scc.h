@@ -118,6 +118,32 @@ int scc_backward_weight(const void* x, const void* dy, void* dw,
                         scc_dtype dtype, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Bytes of device scratch scc_backward needs for this problem (may be 0; 0 as well when the
+ * arguments are invalid, scc_backward then reports the error).
+ */
+size_t scc_backward_workspace_bytes(int N, int Cin, int Cout, int H, int W, int cg, double co,
+                                    scc_dtype dtype);
+
+/*
+ * Both gradients of one layer in one call (Section 4.2, backward pass: the gradients with respect
+ * to the input feature map and to the trainable weights are the two results of a layer's backward
+ * step):
+ *     dx as scc_backward_input computes it, dw as scc_backward_weight computes it.
+ * For fp32 layers whose windows start on multiples of 32 channels and are 64 channels long, with
+ * at most 32 filters per window, H*W a multiple of 4 and 16-byte aligned tensors, one kernel reads
+ * dy and x from memory once and produces both (a third less memory traffic than the two passes;
+ * all products are binary32 products).  Every other layer runs the two passes one after the other.
+ * x: in, N*Cin*H*W.  dy: in, N*Cout*H*W.  w: in, Cout*L.  dx: out, N*Cin*H*W.
+ * dw: out, Cout*L binary32 values (both dtypes).  workspace: device scratch of at least
+ * scc_backward_workspace_bytes(...) bytes, 256-byte aligned, owned by the caller, contents
+ * undefined before and after; may be NULL when the query returns 0.  Two calls on the same inputs
+ * give bitwise identical results.
+ */
+int scc_backward(const void* x, const void* dy, const void* w, void* dx, void* dw,
+                 int N, int Cin, int Cout, int H, int W, int cg, double co,
+                 scc_dtype dtype, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * scc_backward_weight for callers that cannot allocate device memory or hand over a workspace:
  * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
  * arguments, kernels, arithmetic and summation order as scc_backward_weight (results are bitwise

@@ -167,6 +167,40 @@ int scc_backward_weight(const void* x, const void* dy, void* dw, int N, int Cin,
         scc::launch_backward_weight_generic((const scc::bf16_t*)x, (const scc::bf16_t*)dy, (float*)dw, p, st));
 }
 
+size_t scc_backward_workspace_bytes(int N, int Cin, int Cout, int H, int W, int cg, double co, scc_dtype dtype)
+{
+    Problem p;
+    if (make_problem(N, Cin, Cout, H, W, cg, co, &p) != SCC_OK || !dtype_ok(dtype)) return 0;
+    // the fused kernel's need, or that of the separate grad-weight pass it may fall back to, whichever is larger
+    size_t need = scc_backward_weight_workspace_bytes(N, Cin, Cout, H, W, cg, co, dtype);
+    if (dtype == SCC_F32 && scc::backward_fused_eligible(p)) {
+        const size_t fused = scc::backward_fused_workspace(p);
+        need = fused > need ? fused : need;
+    }
+    return need;
+}
+
+int scc_backward(const void* x, const void* dy, const void* w, void* dx, void* dw, int N, int Cin, int Cout, int H,
+                 int W, int cg, double co, scc_dtype dtype, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!x || !dy || !w || !dx || !dw) return SCC_ERR_NULL;
+    Problem p;
+    const int rc = make_problem(N, Cin, Cout, H, W, cg, co, &p);
+    if (rc != SCC_OK) return rc;
+    if (!dtype_ok(dtype)) return SCC_ERR_DTYPE;
+    const size_t need = scc_backward_workspace_bytes(N, Cin, Cout, H, W, cg, co, dtype);
+    if (need > 0 && (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 255u) != 0))
+        return SCC_ERR_WORKSPACE;
+    const bool aligned = (((uintptr_t)x | (uintptr_t)dy | (uintptr_t)dx) & 15u) == 0;
+    if (dtype == SCC_F32 && aligned && scc::backward_fused_eligible(p))
+        return launch_status(scc::launch_backward_fused((const float*)x, (const float*)dy, (const float*)w, (float*)dx,
+                                                        (float*)dw, (float*)workspace, p, (hipStream_t)stream));
+    // every other layer: the two passes one after the other
+    const int r1 = scc_backward_input(dy, w, dx, N, Cin, Cout, H, W, cg, co, dtype, stream);
+    if (r1 != SCC_OK) return r1;
+    return scc_backward_weight(x, dy, dw, N, Cin, Cout, H, W, cg, co, dtype, workspace, workspace_bytes, stream);
+}
+
 int scc_backward_weight_static(const void* x, const void* dy, void* dw, int N, int Cin, int Cout, int H, int W, int cg,
                                double co, scc_dtype dtype, void* stream)
 {

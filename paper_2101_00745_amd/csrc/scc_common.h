@@ -91,4 +91,13 @@ template <typename T>
 hipError_t launch_backward_weight_mfma(const T* x, const T* dy, float* dw, float* workspace, const Problem& p,
                                        hipStream_t st);
 
+// dw[e] = sum over K-splits of part[ks][e], e < count, in a fixed order (scc_mfma_bww.hip)
+hipError_t launch_weight_reduce(const float* part, float* dw, int count, int KS, hipStream_t st);
+
+// Fused backward pass, fp32 (scc_lds_bwd.hip): dx and dw from one read of dy and x
+bool backward_fused_eligible(const Problem& p);
+size_t backward_fused_workspace(const Problem& p);  // bytes of K-split partials (0 when not split)
+hipError_t launch_backward_fused(const float* x, const float* dy, const float* w, float* dx, float* dw,
+                                 float* workspace, const Problem& p, hipStream_t st);
+
 }  // namespace scc

@@ -383,6 +383,12 @@ BwwTiling make_tiling(const Problem& p)
 
 }  // namespace
 
+hipError_t launch_weight_reduce(const float* part, float* dw, int count, int KS, hipStream_t st)
+{
+    backward_weight_reduce<<<dim3((unsigned)((count + 63) / 64)), dim3(256), 0, st>>>(part, dw, count, KS);
+    return hipGetLastError();
+}
+
 bool backward_weight_mfma_eligible(const Problem& p)
 {
     const long long rows = p.Cin > p.Cout ? p.Cin : p.Cout;
@@ -419,9 +425,7 @@ hipError_t launch_backward_weight_mfma(const T_* x, const T_* dy, float* dw, flo
     if (e != hipSuccess) return e;
     e = hipGetLastError();
     if (e != hipSuccess || t.KS == 1) return e;
-    const int count = p.Cout * p.L;
-    backward_weight_reduce<<<dim3((unsigned)((count + 63) / 64)), dim3(256), 0, st>>>(workspace, dw, count, t.KS);
-    return hipGetLastError();
+    return launch_weight_reduce(workspace, dw, p.Cout * p.L, t.KS, st);
 }
 
 template hipError_t launch_backward_weight_mfma<float>(const float*, const float*, float*, float*, const Problem&,

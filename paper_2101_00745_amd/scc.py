@@ -16,6 +16,7 @@ LIB_PATH = os.path.join(_HERE, "libscc_hip.so")
 SCC_F32, SCC_BF16 = 0, 1
 SYMBOLS = ("scc_window_params", "scc_forward", "scc_backward_input",
            "scc_backward_weight_workspace_bytes", "scc_backward_weight", "scc_backward_weight_static",
+           "scc_backward_workspace_bytes", "scc_backward",
            "scc_status_string")
 STATIC_SCRATCH_BYTES = 8 << 20    # SCC_STATIC_SCRATCH_BYTES of include/scc.h
 
@@ -50,6 +51,10 @@ def load():
     lib.scc_backward_weight_workspace_bytes.restype = c_sz
     lib.scc_backward_weight.argtypes = [c_vp, c_vp, c_vp] + shape + [c_vp, c_sz, c_vp]
     lib.scc_backward_weight.restype = c_int
+    lib.scc_backward_workspace_bytes.argtypes = shape
+    lib.scc_backward_workspace_bytes.restype = c_sz
+    lib.scc_backward.argtypes = [c_vp] * 5 + shape + [c_vp, c_sz, c_vp]
+    lib.scc_backward.restype = c_int
     lib.scc_backward_weight_static.argtypes = [c_vp, c_vp, c_vp] + shape + [c_vp]
     lib.scc_backward_weight_static.restype = c_int
     lib.scc_status_string.argtypes = [c_int]
@@ -176,3 +181,37 @@ def scc_backward_weight_static(x, dy, cg, co, out):
         _check(load().scc_backward_weight_static(x.data_ptr(), dy.data_ptr(), out.data_ptr(), N, Cin, Cout, H, W, cg,
                                                  float(co), _dtype_code(x), _stream(dev)))
     return out
+
+
+def scc_backward_workspace_bytes(N, Cin, Cout, H, W, cg, co, dtype=torch.float32):
+    code = SCC_F32 if dtype == torch.float32 else SCC_BF16
+    return int(load().scc_backward_workspace_bytes(N, Cin, Cout, H, W, cg, float(co), code))
+
+
+def scc_backward(x, dy, w, cg, co, out_dx=None, out_dw=None, workspace=None):
+    """(dx, dw) of one layer in one call: x [N,Cin,H,W], dy [N,Cout,H,W], w [Cout,Cin//cg]."""
+    dev = _dev(x, dy, w)
+    N, Cin, H, W = x.shape
+    Cout = dy.shape[1]
+    if dy.dtype != x.dtype or dy.shape != (N, Cout, H, W):
+        raise ValueError("dy must be [N,Cout,H,W] with the dtype of x")
+    if w.dtype != x.dtype or w.dim() != 2 or w.shape[0] != Cout or \
+            (cg >= 1 and Cin % cg == 0 and w.shape[1] != Cin // cg):
+        raise ValueError("w must be [Cout, Cin//cg] with the dtype of x")
+    code = _dtype_code(x)
+    need = int(load().scc_backward_workspace_bytes(N, Cin, Cout, H, W, cg, float(co), code))
+    if workspace is None and need > 0:
+        workspace = torch.empty(need, dtype=torch.uint8, device=dev)
+    L = Cin // cg if cg >= 1 and Cin % cg == 0 else 1
+    dx = torch.empty_like(x) if out_dx is None else out_dx
+    dw = torch.empty((Cout, L), dtype=torch.float32, device=dev) if out_dw is None else out_dw
+    for o, shp, dt in ((out_dx, x.shape, x.dtype), (out_dw, (Cout, L), torch.float32)):
+        if o is not None:
+            _dev(o)
+            assert o.shape == shp and o.dtype == dt
+    ws_ptr = workspace.data_ptr() if workspace is not None else None
+    ws_len = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    with torch.cuda.device(dev):
+        _check(load().scc_backward(x.data_ptr(), dy.data_ptr(), w.data_ptr(), dx.data_ptr(), dw.data_ptr(), N, Cin, Cout,
+                                   H, W, cg, float(co), code, ws_ptr, ws_len, _stream(dev)))
+    return dx, dw
