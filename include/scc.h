@@ -25,11 +25,22 @@
  *   - Outputs are overwritten, never accumulated into.  An output must not
  *     alias an input.
  *   - dtype SCC_F32: all tensors are IEEE binary32 and all sums are binary32.
- *     Products are binary32 products, or (forward and grad-input on the matrix
- *     cores) six of the nine partial products of an exact three-way bfloat16
- *     split of both factors, which differ from the binary32 product by less
- *     than 2^-23 of it.  Inf or NaN inputs may give NaN where binary32
- *     arithmetic would give Inf.
+ *     Products are binary32 products, or (forward, grad-input and the fused
+ *     backward on the matrix cores) six of the nine partial products of an
+ *     exact three-way bfloat16 split of both factors, which differ from the
+ *     binary32 product by less than 2^-23 of it.
+ *     Finite inputs: a filter never sees a channel outside its window, and
+ *     all-zero weights give exact zeros.  Non-finite inputs: an Inf or NaN
+ *     element gives NaN where binary32 arithmetic would give Inf, and in the
+ *     forward and grad-input passes it may also turn outputs of OTHER filters
+ *     or channels at the same sample and pixel into NaN (inside a tile zero
+ *     weights multiply it); it never reaches another sample or pixel.  In
+ *     grad-weight, which sums over all samples and pixels, it may reach any
+ *     weight gradient.
+ *     Operands below about 2^-110 in magnitude lose the low pieces of the
+ *     split to underflow: the error is then bounded by a fraction of the
+ *     smallest normal number instead of 2^-23 of the product (scc_backward_weight
+ *     multiplies in binary32 and is not affected).
  *     dtype SCC_BF16: x, w, y, dy, dx are bfloat16 (upper half of a binary32,
  *     results rounded to nearest even), products accumulated in binary32;
  *     dw is written as binary32 in BOTH dtypes.

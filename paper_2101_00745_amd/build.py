@@ -7,6 +7,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 LIB = os.path.join(HERE, "libscc_hip.so")
+MEMBW_SRC = os.path.join(CSRC, "membw", "membw.hip")
+MEMBW_LIB = os.path.join(HERE, "libscc_membw.so")   # streaming kernels of the benchmark's copy ceiling; not the SCC ABI
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 COMPILE_FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-fno-gpu-rdc",
@@ -66,5 +68,16 @@ def build(force=True, verbose=False):
     return LIB
 
 
+def build_membw(force=True, verbose=False):
+    """Build libscc_membw.so, the plain copy / read kernels bench.py measures its copy ceiling with."""
+    if not force and os.path.exists(MEMBW_LIB) and os.path.getmtime(MEMBW_LIB) >= os.path.getmtime(MEMBW_SRC):
+        return MEMBW_LIB
+    tmp = MEMBW_LIB + ".tmp.%d" % os.getpid()
+    _run([HIPCC] + COMPILE_FLAGS + ["-shared", "-o", tmp, MEMBW_SRC], verbose)
+    os.replace(tmp, MEMBW_LIB)
+    return MEMBW_LIB
+
+
 if __name__ == "__main__":
     print(build(force=True, verbose=True))
+    print(build_membw(force=True, verbose=True))

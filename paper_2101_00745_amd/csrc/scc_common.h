@@ -58,19 +58,29 @@ mfma_bf16(const uint32_t (&a)[KC / 2], const uint32_t (&b)[KC / 2], float __attr
 // Exact split of KC binary32 values into bf16 pieces: v = hi + mid + lo with hi = v truncated to bf16,
 // mid = (v - hi) truncated, lo = v - hi - mid (at most 8 significant bits left, so it is a bf16 value).
 // Pieces of values 2e and 2e+1 are packed into one register, low half first, as mfma_bf16 takes them.
+// Seven vector instructions per pair of values: a byte permute packs the two upper halves (the truncations),
+// and v_dot2c_f32_bf16 (d += a.lo*b.lo + a.hi*b.hi on packed bf16 pairs) with b = (-1, -0) or (-0, -1)
+// subtracts one half of the packed pair from the binary32 value it was cut from: an exact subtraction, the
+// other half only adds a signed zero.  (The constants carry -0.0 in the unused half so that they are literals:
+// as an inline constant -1.0 the operand was observed to reach the wrong half.)
 template <int KC, typename F>
 __device__ __forceinline__ void split3(F get, uint32_t (&hi)[KC / 2], uint32_t (&mid)[KC / 2], uint32_t (&lo)[KC / 2])
 {
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    const bf16x2 kLow = __builtin_bit_cast(bf16x2, 0x8000bf80u);    // (-1.0, -0.0): minus the value in the low half
+    const bf16x2 kHigh = __builtin_bit_cast(bf16x2, 0xbf808000u);   // (-0.0, -1.0): minus the value in the high half
 #pragma unroll
     for (int e = 0; e < KC / 2; ++e) {
         const float v0 = get(2 * e), v1 = get(2 * e + 1);
-        const float r0 = v0 - __uint_as_float(__float_as_uint(v0) & 0xffff0000u);
-        const float r1 = v1 - __uint_as_float(__float_as_uint(v1) & 0xffff0000u);
-        const float l0 = r0 - __uint_as_float(__float_as_uint(r0) & 0xffff0000u);
-        const float l1 = r1 - __uint_as_float(__float_as_uint(r1) & 0xffff0000u);
         // upper halves of (x1, x0) side by side: bytes 2,3 of x0 then bytes 2,3 of x1
         hi[e] = __builtin_amdgcn_perm(__float_as_uint(v1), __float_as_uint(v0), 0x07060302u);
+        const bf16x2 h2 = __builtin_bit_cast(bf16x2, hi[e]);
+        const float r0 = __builtin_amdgcn_fdot2_f32_bf16(h2, kLow, v0, false);
+        const float r1 = __builtin_amdgcn_fdot2_f32_bf16(h2, kHigh, v1, false);
         mid[e] = __builtin_amdgcn_perm(__float_as_uint(r1), __float_as_uint(r0), 0x07060302u);
+        const bf16x2 m2 = __builtin_bit_cast(bf16x2, mid[e]);
+        const float l0 = __builtin_amdgcn_fdot2_f32_bf16(m2, kLow, r0, false);
+        const float l1 = __builtin_amdgcn_fdot2_f32_bf16(m2, kHigh, r1, false);
         lo[e] = __builtin_amdgcn_perm(__float_as_uint(l1), __float_as_uint(l0), 0x07060302u);
     }
 }

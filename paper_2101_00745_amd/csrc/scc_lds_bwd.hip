@@ -222,19 +222,26 @@ __global__ __launch_bounds__(kWaves * 64) void backward_fused_lds32(const float*
         f32x16 acc, acc2;
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[v] = acc2[v] = 0.f;
+        // all 32 operand values of the tile are requested from LDS at once; then the pieces of K group gk+1 are
+        // cut (vector ALU) while the matrix instructions of group gk run
+        float bv[4][8];
+#pragma unroll
+        for (int gk = 0; gk < 4; ++gk)
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                bv[gk][e] = *(const float*)(sb + dx_rd + (16 * gk + e) * 128 + 16 * (dx_piece ^ e));
+        uint32_t bh[2][4], bm[2][4], bl[2][4];
+        split3<8>([&](int e) { return bv[0][e]; }, bh[0], bm[0], bl[0]);
 #pragma unroll
         for (int gk = 0; gk < 4; ++gk) {
-            float bv[8];
-#pragma unroll
-            for (int e = 0; e < 8; ++e) bv[e] = *(const float*)(sb + dx_rd + (16 * gk + e) * 128 + 16 * (dx_piece ^ e));
-            uint32_t bh[4], bm[4], bl[4];
-            split3<8>([&](int e) { return bv[e]; }, bh, bm, bl);
-            acc = mfma_bf16<8>(a_lo[gk], bh, acc);
-            acc2 = mfma_bf16<8>(a_hi[gk], bl, acc2);
-            acc = mfma_bf16<8>(a_mid[gk], bm, acc);
-            acc2 = mfma_bf16<8>(a_mid[gk], bh, acc2);
-            acc = mfma_bf16<8>(a_hi[gk], bm, acc);
-            acc2 = mfma_bf16<8>(a_hi[gk], bh, acc2);
+            const int cur = gk & 1, nxt = cur ^ 1;
+            if (gk + 1 < 4) split3<8>([&](int e) { return bv[gk + 1][e]; }, bh[nxt], bm[nxt], bl[nxt]);
+            acc = mfma_bf16<8>(a_lo[gk], bh[cur], acc);
+            acc2 = mfma_bf16<8>(a_hi[gk], bl[cur], acc2);
+            acc = mfma_bf16<8>(a_mid[gk], bm[cur], acc);
+            acc2 = mfma_bf16<8>(a_mid[gk], bh[cur], acc2);
+            acc = mfma_bf16<8>(a_hi[gk], bm[cur], acc);
+            acc2 = mfma_bf16<8>(a_hi[gk], bh[cur], acc2);
         }
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[v] += acc2[v];
@@ -256,24 +263,45 @@ __global__ __launch_bounds__(kWaves * 64) void backward_fused_lds32(const float*
     };
     auto compute_dw = [&](int buf) {
         const char* sb = (const char*)lds + buf * kBufB + sub_ofs;
+        // all operand rows of the chunk are requested from LDS at once (12 reads of 16 bytes per lane); then the
+        // pieces of K group 1 are cut while the matrix instructions of group 0 run
+        f32x4 ra[2][2], rb[2][2][2];           // [K group][16-byte piece], [K group][position tile][piece]
 #pragma unroll
         for (int gk = 0; gk < 2; ++gk) {
             const int p0 = 16 * ((4 * gk + 2 * h) ^ (f & 7)), p1 = 16 * ((4 * gk + 2 * h + 1) ^ (f & 7));
-            const f32x4 a0 = *(const f32x4*)(sb + dw_a + p0), a1 = *(const f32x4*)(sb + dw_a + p1);
-            uint32_t ah[4], am[4], al[4];
-            split3<8>([&](int e) { return e < 4 ? a0[e] : a1[e - 4]; }, ah, am, al);
+            ra[gk][0] = *(const f32x4*)(sb + dw_a + p0);
+            ra[gk][1] = *(const f32x4*)(sb + dw_a + p1);
 #pragma unroll
             for (int c = 0; c < 2; ++c) {
-                const f32x4 b0 = *(const f32x4*)(sb + dw_b + c * 32 * 128 + p0), b1 = *(const f32x4*)(sb + dw_b + c * 32 * 128 + p1);
-                uint32_t bh[4], bm[4], bl[4];
-                split3<8>([&](int e) { return e < 4 ? b0[e] : b1[e - 4]; }, bh, bm, bl);
-                acc_w[c] = mfma_bf16<8>(al, bh, acc_w[c]);
-                acc_w[c] = mfma_bf16<8>(ah, bl, acc_w[c]);
-                acc_w[c] = mfma_bf16<8>(am, bm, acc_w[c]);
-                acc_w[c] = mfma_bf16<8>(am, bh, acc_w[c]);
-                acc_w[c] = mfma_bf16<8>(ah, bm, acc_w[c]);
-                acc_w[c] = mfma_bf16<8>(ah, bh, acc_w[c]);
+                rb[gk][c][0] = *(const f32x4*)(sb + dw_b + c * 32 * 128 + p0);
+                rb[gk][c][1] = *(const f32x4*)(sb + dw_b + c * 32 * 128 + p1);
             }
+        }
+        uint32_t ah[2][4], am[2][4], al[2][4], bh[2][2][4], bm[2][2][4], bl[2][2][4];
+        auto cut = [&](int gk) {
+            split3<8>([&](int e) { return e < 4 ? ra[gk][0][e] : ra[gk][1][e - 4]; }, ah[gk], am[gk], al[gk]);
+#pragma unroll
+            for (int c = 0; c < 2; ++c)
+                split3<8>([&](int e) { return e < 4 ? rb[gk][c][0][e] : rb[gk][c][1][e - 4]; }, bh[gk][c], bm[gk][c],
+                          bl[gk][c]);
+        };
+        cut(0);
+#pragma unroll
+        for (int gk = 0; gk < 2; ++gk) {
+            if (gk == 0) cut(1);
+            // the two position tiles take turns, so that no matrix instruction waits for the one right before it
+            acc_w[0] = mfma_bf16<8>(al[gk], bh[gk][0], acc_w[0]);
+            acc_w[1] = mfma_bf16<8>(al[gk], bh[gk][1], acc_w[1]);
+            acc_w[0] = mfma_bf16<8>(ah[gk], bl[gk][0], acc_w[0]);
+            acc_w[1] = mfma_bf16<8>(ah[gk], bl[gk][1], acc_w[1]);
+            acc_w[0] = mfma_bf16<8>(am[gk], bm[gk][0], acc_w[0]);
+            acc_w[1] = mfma_bf16<8>(am[gk], bm[gk][1], acc_w[1]);
+            acc_w[0] = mfma_bf16<8>(am[gk], bh[gk][0], acc_w[0]);
+            acc_w[1] = mfma_bf16<8>(am[gk], bh[gk][1], acc_w[1]);
+            acc_w[0] = mfma_bf16<8>(ah[gk], bm[gk][0], acc_w[0]);
+            acc_w[1] = mfma_bf16<8>(ah[gk], bm[gk][1], acc_w[1]);
+            acc_w[0] = mfma_bf16<8>(ah[gk], bh[gk][0], acc_w[0]);
+            acc_w[1] = mfma_bf16<8>(ah[gk], bh[gk][1], acc_w[1]);
         }
     };
 

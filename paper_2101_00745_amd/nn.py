@@ -1,7 +1,8 @@
 """Drop-in PyTorch layer over the SCC C ABI (the paper's third contribution: SCC as a replacement of the
 pointwise convolution inside a depthwise-separable block, trainable end to end).
 
-``SCCFunction`` routes autograd through ``scc_forward`` / ``scc_backward_input`` / ``scc_backward_weight``;
+``SCCFunction`` routes autograd through ``scc_forward`` and ``scc_backward`` (or the single-gradient calls when
+only one gradient is wanted);
 ``SCC`` is the module (weight ``[Cout, Cin//cg]``, optional bias).  All SCC arithmetic runs in the HIP kernels;
 the bias, which Section 4.2 only mentions among the trainable parameters, is a broadcast add / a sum over
 (N, H, W) done with ordinary tensor ops.  Tensors must be CUDA, contiguous NCHW, float32 or bfloat16.
@@ -27,10 +28,14 @@ class SCCFunction(torch.autograd.Function):
         x, weight = ctx.saved_tensors
         dy = dy.contiguous()
         dx = dw = None
-        if ctx.needs_input_grad[0]:
+        if ctx.needs_input_grad[0] and ctx.needs_input_grad[1]:
+            dx, dw = _scc.scc_backward(x, dy, weight, ctx.cg, ctx.co)      # one call, dy and x read once where fused
+        elif ctx.needs_input_grad[0]:
             dx = _scc.scc_backward_input(dy, weight, x.shape[1], ctx.cg, ctx.co)
-        if ctx.needs_input_grad[1]:
-            dw = _scc.scc_backward_weight(x, dy, ctx.cg, ctx.co).to(weight.dtype)   # dw comes back as float32
+        elif ctx.needs_input_grad[1]:
+            dw = _scc.scc_backward_weight(x, dy, ctx.cg, ctx.co)
+        if dw is not None:
+            dw = dw.to(weight.dtype)                                        # dw comes back as float32
         return dx, dw, None, None
 
 

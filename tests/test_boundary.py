@@ -29,7 +29,7 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_status_strings():
-    for code in range(0, -7, -1):
+    for code in range(0, -8, -1):
         s = S.scc_status_string(code)
         assert s.startswith("SCC_")
     assert "unknown" in S.scc_status_string(-99)
@@ -85,17 +85,22 @@ def _call(which, **over):
         return lib.scc_forward(FAKE, FAKE, FAKE, *shape, None)
     if which == "bwi":
         return lib.scc_backward_input(FAKE, FAKE, FAKE, *shape, None)
+    if which == "bwd":
+        return lib.scc_backward(FAKE, FAKE, FAKE, FAKE, FAKE, *shape, None, 0, None)
+    if which == "bww_static":
+        return lib.scc_backward_weight_static(FAKE, FAKE, FAKE, *shape, None)
     return lib.scc_backward_weight(FAKE, FAKE, FAKE, *shape, None, 0, None)
 
 
-@pytest.mark.parametrize("which", ["fwd", "bwi", "bww"])
+@pytest.mark.parametrize("which", ["fwd", "bwi", "bww", "bwd", "bww_static"])
 @pytest.mark.parametrize("over,exc,code", BAD)
 def test_invalid_arguments_are_rejected_on_the_host(which, over, exc, code):
     assert _call(which, **over) == code
     shape = dict(N=2, Cin=8, Cout=6, H=3, W=3, cg=2, co=0.5, dtype=0)
     shape.update(over)
-    assert S.load().scc_backward_weight_workspace_bytes(*[shape[k] for k in
-                                                         ("N", "Cin", "Cout", "H", "W", "cg", "co", "dtype")]) == 0
+    args = [shape[k] for k in ("N", "Cin", "Cout", "H", "W", "cg", "co", "dtype")]
+    assert S.load().scc_backward_weight_workspace_bytes(*args) == 0
+    assert S.load().scc_backward_workspace_bytes(*args) == 0
 
 
 def test_null_pointers_are_rejected():
@@ -107,6 +112,22 @@ def test_null_pointers_are_rejected():
         assert lib.scc_forward(*ptrs, *shape, None) == -1
         assert lib.scc_backward_input(*ptrs, *shape, None) == -1
         assert lib.scc_backward_weight(*ptrs, *shape, None, 0, None) == -1
+        assert lib.scc_backward_weight_static(*ptrs, *shape, None) == -1
+    for i in range(5):
+        ptrs = [FAKE] * 5
+        ptrs[i] = None
+        assert lib.scc_backward(*ptrs, *shape, None, 0, None) == -1
+
+
+def test_backward_workspace_is_checked_on_the_host():
+    # a layer the fused backward kernel takes: it needs K-split scratch, and a call without it is refused
+    lib = S.load()
+    shape = (64, 256, 256, 16, 16, 4, 0.5, 0)
+    need = lib.scc_backward_workspace_bytes(*shape)
+    assert need > 0 and need >= lib.scc_backward_weight_workspace_bytes(*shape)
+    assert lib.scc_backward(FAKE, FAKE, FAKE, FAKE, FAKE, *shape, None, 0, None) == -5
+    assert lib.scc_backward(FAKE, FAKE, FAKE, FAKE, FAKE, *shape, FAKE, need - 1, None) == -5
+    assert lib.scc_backward(FAKE, FAKE, FAKE, FAKE, FAKE, *shape, ctypes.c_void_p(0x1004), need, None) == -5
 
 
 def test_binding_refuses_cpu_tensors():

@@ -22,29 +22,20 @@ GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
 # independent index generators
 # ----------------------------------------------------------------------------------------
 def paper_windows(Cin, Cout, cg, co):
-    """Algorithm 1 (one cycle of (start, end) pairs, stop at the first repeat) followed by
-    Algorithm 2's lookup (filter k takes entry k mod cyclic_dist).  Returns (starts, dist).
-
-    One reading is applied: the listing initialises the first pair's end to group_width
-    without the "% Cin" every later pair gets.  The two differ only for cg = 1
-    (group_width = Cin), where the unreduced (0, Cin) would not be recognised as the same
-    window as its own return (0, 0) and the cycle would be counted one too long.  The
-    first end is reduced like the others, so a window is identified by where it starts."""
-    seen, order = set(), []
-    gw = Cin // cg
-    start, end = 0, gw % Cin
-    start_v, end_v = start, end
-    for _ in range(Cout):
-        item = (start, end)
-        if item in seen:
-            break
-        seen.add(item)
-        order.append(item)
-        start_v = end_v - int(co * gw)
-        end_v = start_v + gw
-        start, end = start_v % Cin, end_v % Cin
-    dist = len(order)
-    return [order[k % dist][0] for k in range(Cout)], dist
+    """Window starts as Algorithm 1 and Algorithm 2 define them, restated in a form of its own (and a
+    different one from the oracle's): a window begins where the previous one ended, stepped back by the
+    overlap in channels; positions are reduced modulo Cin; the list of distinct windows ends at the first
+    start that has been seen before (its length is the cyclic distance), and filter k takes window
+    k mod distance.  A window is identified by where it starts: for cg = 1 the pair (start, end) of
+    Algorithm 1 would tell (0, Cin) and (0, 0) apart although they are the same window.
+    Returns (starts, distance)."""
+    width = Cin // cg
+    back = int(co * width)
+    cycle, pos = [], 0
+    while len(cycle) < Cout and pos % Cin not in cycle:
+        cycle.append(pos % Cin)
+        pos = pos + width - back          # end of this window, minus the overlap
+    return [cycle[k % len(cycle)] for k in range(Cout)], len(cycle)
 
 
 def window_channels(Cin, Cout, cg, co):
