@@ -58,6 +58,10 @@ def parse():
     ap.add_argument("--sweep", default="", metavar="FILE.json",
                     help="also time every configuration (overlap sweep, 14x14 layer fp32/bf16, expanding layer, "
                          "13-layer stack, group-count and batch sweeps) pass by pass and write the table to this file")
+    ap.add_argument("--dispatch-trace", action="store_true",
+                    help="run every configuration's entry points once each, a 16-byte membw_read launch before each "
+                         "as a separator, and print the order: under `rocprofv3 --kernel-trace` the trace then shows "
+                         "which kernels every configuration dispatched")
     return ap.parse_args()
 
 
@@ -251,13 +255,8 @@ def oracle_step_seconds(Wk, layer, seconds, max_reps=200, sample_n=None):
 
 def sweep(S, Wk, torch, steps, warmup, path):
     """Every configuration of the build, each pass timed on its own; written to `path` and to stderr."""
-    cases = [(l, torch.float32) for l in Wk.METRIC_SWEEP] + [(Wk.LATE, torch.float32), (Wk.LATE, torch.bfloat16),
-                                                             (Wk.EXPAND, torch.float32)]
-    cases += [(l, torch.float32) for l in Wk.STACK]
-    cases += [(l, torch.float32) for l in Wk.CG_SWEEP] + [(l, torch.float32) for l in Wk.BATCH_SWEEP]
-    cases += [(l, torch.bfloat16) for l in [Wk.METRIC, Wk.EXPAND, Wk.BATCH_SWEEP[0], Wk.BATCH_SWEEP[-1]]]
     rows = []
-    for layer, dtype in cases:
+    for layer, dtype in all_cases(Wk, torch):
         esz = 4 if dtype == torch.float32 else 2
         _, r = measure(S, Wk, torch, layer, dtype, steps, warmup, whole_step=False)
         us = {k: v * 1e3 for k, v in r["per_pass_ms"].items()}
@@ -291,6 +290,35 @@ def sweep(S, Wk, torch, steps, warmup, path):
           file=sys.stderr, flush=True)
 
 
+def all_cases(Wk, torch):
+    cases = [(l, torch.float32) for l in Wk.METRIC_SWEEP] + [(Wk.LATE, torch.float32), (Wk.LATE, torch.bfloat16),
+                                                             (Wk.EXPAND, torch.float32)]
+    cases += [(l, torch.float32) for l in Wk.STACK]
+    cases += [(l, torch.float32) for l in Wk.CG_SWEEP] + [(l, torch.float32) for l in Wk.BATCH_SWEEP]
+    cases += [(l, torch.bfloat16) for l in [Wk.METRIC, Wk.EXPAND, Wk.BATCH_SWEEP[0], Wk.BATCH_SWEEP[-1]]]
+    return cases
+
+
+def dispatch_trace(S, Wk, torch, copy_lib):
+    """One call of every entry point per configuration, separated by a 16-byte membw_read launch."""
+    dev = torch.device("cuda:0")
+    sink = torch.zeros(64, dtype=torch.float32, device=dev)
+    order = []
+    for layer, dtype in all_cases(Wk, torch):
+        x, w, dy = Wk.make_inputs(layer)
+        xd, wd, dyd = (torch.from_numpy(a).to(dtype).to(dev) for a in (x, w, dy))
+        for name, fn in (("scc_forward", lambda: S.scc_forward(xd, wd, layer.cg, layer.co)),
+                         ("scc_backward_input", lambda: S.scc_backward_input(dyd, wd, layer.Cin, layer.cg, layer.co)),
+                         ("scc_backward_weight", lambda: S.scc_backward_weight(xd, dyd, layer.cg, layer.co)),
+                         ("scc_backward", lambda: S.scc_backward(xd, dyd, wd, layer.cg, layer.co))):
+            copy_lib.membw_read_bytes(sink.data_ptr(), sink.data_ptr() + 64, 16, None)
+            fn()
+            torch.cuda.synchronize()
+            order.append("%s %s %s" % (layer.name, "f32" if dtype == torch.float32 else "bf16", name))
+        del xd, wd, dyd
+    print("\n".join(order), flush=True)
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -306,6 +334,9 @@ def main():
         sys.exit(2)
     S.load()
     copy_lib = load_membw()
+    if args.dispatch_trace:
+        dispatch_trace(S, Wk, torch, copy_lib)
+        return
     if args.sweep:
         sweep(S, Wk, torch, min(args.steps, 64), min(args.warmup, 8), args.sweep)
     layer, dtype = pick_workload(args.workload)

@@ -49,6 +49,9 @@
  *   - Return value: SCC_OK, or a negative scc_status.  Everything except
  *     SCC_ERR_LAUNCH is decided on the host before any GPU call is made, so an
  *     invalid call touches no memory.  Nothing is printed, nothing aborts.
+ *     A call that launches first discards any error an earlier HIP call of the
+ *     process left pending (hipGetLastError), so SCC_ERR_LAUNCH always refers
+ *     to this call's own kernels.
  *   - co is a double so that int(co * L) truncates exactly as Algorithm 1 does.
  */
 #ifndef SCC_H

@@ -57,6 +57,11 @@ bool dtype_ok(scc_dtype d) { return d == SCC_F32 || d == SCC_BF16; }
 
 int launch_status(hipError_t e) { return e == hipSuccess ? SCC_OK : SCC_ERR_LAUNCH; }
 
+// The launchers report hipGetLastError(), which also returns (and clears) an error an EARLIER, unrelated call of
+// the process left behind.  Every entry point that launches drops such a leftover first, so that SCC_ERR_LAUNCH
+// always speaks of this call's own kernels.
+void drop_stale_error() { (void)hipGetLastError(); }
+
 // Device address of `scratch` on the current device, resolved once per device (each GPU holds its own copy
 // of the array at its own address).
 constexpr int kMaxDevices = 64;
@@ -100,6 +105,7 @@ int scc_forward(const void* x, const void* w, void* y, int N, int Cin, int Cout,
     const int rc = make_problem(N, Cin, Cout, H, W, cg, co, &p);
     if (rc != SCC_OK) return rc;
     if (!dtype_ok(dtype)) return SCC_ERR_DTYPE;
+    drop_stale_error();
     hipStream_t st = (hipStream_t)stream;
     if (dtype == SCC_F32) {
         if (scc::forward_mfma_eligible(p))
@@ -121,6 +127,7 @@ int scc_backward_input(const void* dy, const void* w, void* dx, int N, int Cin, 
     const int rc = make_problem(N, Cin, Cout, H, W, cg, co, &p);
     if (rc != SCC_OK) return rc;
     if (!dtype_ok(dtype)) return SCC_ERR_DTYPE;
+    drop_stale_error();
     hipStream_t st = (hipStream_t)stream;
     if (dtype == SCC_F32) {
         if (scc::backward_input_mfma_eligible(p))
@@ -153,6 +160,7 @@ int scc_backward_weight(const void* x, const void* dy, void* dw, int N, int Cin,
     const size_t need = scc_backward_weight_workspace_bytes(N, Cin, Cout, H, W, cg, co, dtype);
     if (need > 0 && (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 255u) != 0))
         return SCC_ERR_WORKSPACE;
+    drop_stale_error();
     hipStream_t st = (hipStream_t)stream;
     if (dtype == SCC_F32) {
         if (scc::backward_weight_mfma_eligible(p))
@@ -191,6 +199,7 @@ int scc_backward(const void* x, const void* dy, const void* w, void* dx, void* d
     const size_t need = scc_backward_workspace_bytes(N, Cin, Cout, H, W, cg, co, dtype);
     if (need > 0 && (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 255u) != 0))
         return SCC_ERR_WORKSPACE;
+    drop_stale_error();
     const bool aligned = (((uintptr_t)x | (uintptr_t)dy | (uintptr_t)dx) & 15u) == 0;
     if (dtype == SCC_F32 && aligned && scc::backward_fused_eligible(p))
         return launch_status(scc::launch_backward_fused((const float*)x, (const float*)dy, (const float*)w, (float*)dx,

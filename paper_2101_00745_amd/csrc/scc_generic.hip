@@ -28,8 +28,9 @@ __global__ __launch_bounds__(kWaves * 64) void forward_generic(const T* __restri
     const int n = (int)(qc / P.HW), p = (int)(qc % P.HW);
     const T* xcol = x + (long long)n * P.Cin * P.HW + p;
     T* ycol = y + (long long)n * P.Cout * P.HW + p;
-    const int k_end = min(P.Cout, ((int)blockIdx.y + 1) * kRowsPerBlock);
-    for (int k = blockIdx.y * kRowsPerBlock + wave_id(); k < k_end; k += kWaves) {
+    for (int k0 = blockIdx.y * kRowsPerBlock; k0 < P.Cout; k0 += gridDim.y * kRowsPerBlock) {   // grid.y is capped
+    const int k_end = min(P.Cout, k0 + kRowsPerBlock);
+    for (int k = k0 + wave_id(); k < k_end; k += kWaves) {
         int c = (int)(((long long)k * P.stride) % P.Cin);  // window start, uniform
         const T* wk = w + (long long)k * P.L;
         float acc = 0.f;
@@ -38,6 +39,7 @@ __global__ __launch_bounds__(kWaves * 64) void forward_generic(const T* __restri
             c = (c + 1 == P.Cin) ? 0 : c + 1;
         }
         if (live) ycol[(long long)k * P.HW] = from_f32<T>(acc);
+    }
     }
 }
 
@@ -54,8 +56,9 @@ __global__ __launch_bounds__(kWaves * 64) void backward_input_generic(const T* _
     const int n = (int)(qc / P.HW), p = (int)(qc % P.HW);
     const T* gcol = dy + (long long)n * P.Cout * P.HW + p;
     T* dcol = dx + (long long)n * P.Cin * P.HW + p;
-    const int c_end = min(P.Cin, ((int)blockIdx.y + 1) * kRowsPerBlock);
-    for (int c = blockIdx.y * kRowsPerBlock + wave_id(); c < c_end; c += kWaves) {
+    for (int c0 = blockIdx.y * kRowsPerBlock; c0 < P.Cin; c0 += gridDim.y * kRowsPerBlock) {     // grid.y is capped
+    const int c_end = min(P.Cin, c0 + kRowsPerBlock);
+    for (int c = c0 + wave_id(); c < c_end; c += kWaves) {
         float acc = 0.f;
         int j = c;  // (c - s_0) mod Cin with s_0 = 0
         for (int k = 0; k < P.Cout; ++k) {
@@ -64,6 +67,7 @@ __global__ __launch_bounds__(kWaves * 64) void backward_input_generic(const T* _
             if (j < 0) j += P.Cin;
         }
         if (live) dcol[(long long)c * P.HW] = from_f32<T>(acc);
+    }
     }
 }
 
@@ -90,7 +94,9 @@ __global__ __launch_bounds__(kWaves * 64) void backward_weight_generic(const T* 
 
 inline dim3 column_grid(const Problem& p, int rows)
 {
-    return dim3((unsigned)((p.NQ + 63) / 64), (unsigned)((rows + kRowsPerBlock - 1) / kRowsPerBlock), 1);
+    // grid.y may not exceed 65535: the kernels stride over the row blocks beyond that
+    const long long row_blocks = (rows + kRowsPerBlock - 1) / kRowsPerBlock;
+    return dim3((unsigned)((p.NQ + 63) / 64), (unsigned)(row_blocks < 65535 ? row_blocks : 65535), 1);
 }
 
 }  // namespace
