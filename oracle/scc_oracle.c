@@ -72,19 +72,19 @@ int scc_oracle_window(int Cin, int cg, double co, int *L_out, int *ov_out)
     return 0;
 }
 
-/* Window start of every filter, produced by walking Algorithm 1's virtual
- * (start_v, end_v) pair filter by filter and reducing modulo Cin.  The
- * dictionary of Algorithm 1 only detects the period; Algorithm 2 indexes it
- * with k mod cyclic_dist, which reproduces this same walk. */
+/* Window start of every filter.  Algorithm 1 places each filter's window
+ * L - ov channels after the previous one along an unbounded channel axis and
+ * folds positions into [0, Cin); its dictionary only detects when the folded
+ * windows repeat, and Algorithm 2 indexes it with k mod cyclic_dist, which
+ * gives filter k the k-th position of this same sequence. */
 int scc_oracle_starts(int Cin, int Cout, int cg, double co, int *start)
 {
     int L, ov;
     if (scc_oracle_window(Cin, cg, co, &L, &ov) != 0 || Cout <= 0) return -1;
-    long long start_v = 0, end_v = L;
+    long long unfolded = 0;
     for (int k = 0; k < Cout; ++k) {
-        start[k] = (int)(start_v % Cin);
-        start_v = end_v - ov;
-        end_v = start_v + L;
+        start[k] = (int)(unfolded % Cin);
+        unfolded += L - ov;
     }
     return 0;
 }
