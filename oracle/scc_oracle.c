@@ -25,6 +25,11 @@
  *   grad-weight       - Section 4.2 names the gradient of the trainable weights
  *                       without describing a kernel; it is the derivative of
  *                       the forward definition with respect to w.
+ *   depthwise 3x3     - Eq. 2 (Section 2.2): channel a of the output is the
+ *                       3x3 spatial filter of channel a applied to channel a of
+ *                       the input, the tap (i, j) reading the pixel
+ *                       (m + i - 1, n + j - 1); it is the stage whose output the
+ *                       SCC consumes in a DW + SCC block (Section 3.1).
  *
  * Readings taken where the paper is silent:
  *   - overlap in channels is int(co * group_width) with C truncation of the
@@ -32,13 +37,23 @@
  *   - weight j of filter k multiplies the j-th channel of the window counted
  *     from the window start, wrapping past the last channel to channel 0;
  *   - Cin must be divisible by cg.
+ *   - Eq. 2: the taps are i, j in {0, 1, 2}, so the filter is centred on the
+ *     output pixel; pixels outside the feature map count as zero (the paper keeps
+ *     the spatial size of feature maps across a layer); no flip of the filter
+ *     (the equation multiplies tap (i, j) with the pixel offset by (i-1, j-1));
+ *     a spatial stride s (the paper's CNNs halve the feature map in some
+ *     depthwise stages, the equation has none) centres output pixel (m, n) on
+ *     input pixel (s*m, s*n), which gives floor((H-1)/s)+1 output rows.
  *
- * Layout: x[N][Cin][HW], y[N][Cout][HW], w[Cout][L], all dense row-major.
+ * Layout: x[N][Cin][HW], y[N][Cout][HW], w[Cout][L], depthwise filters
+ * kdw[C][3][3], all dense row-major.
  *
  * Pinning status (tests/test_oracle_pins.py): every function here is pinned
  * against the paper's worked example, library convolutions for the special
  * cases, the channel-stack composition, dense brute force, invariants and
- * finite differences.  Nothing in this file is "parity unpinned".
+ * finite differences; the depthwise stage against a library grouped
+ * convolution, one-tap filters (pure shifts), tap counts at the border and a
+ * dense matrix built tap by tap.  Nothing in this file is "parity unpinned".
  */
 #include <stddef.h>
 #include <stdlib.h>
@@ -166,5 +181,44 @@ int scc_oracle_backward_weight(const double *x, const double *dy, double *dw,
         }
     }
     free(s);
+    return 0;
+}
+
+/* Output rows (or columns) of the depthwise stage for an input of `size` rows
+ * and spatial stride `stride`. */
+int scc_oracle_depthwise_out(int size, int stride)
+{
+    if (size <= 0 || stride <= 0) return -1;
+    return (size - 1) / stride + 1;
+}
+
+/* z[n,a,m,q] = sum_{i,j in 0..2} kdw[a,i,j] * x[n,a, stride*m + i - 1, stride*q + j - 1],
+ * pixels outside the H x W map counting as zero (Eq. 2). */
+int scc_oracle_depthwise3x3(const double *x, const double *kdw, double *z,
+                            int N, int C, int H, int W, int stride)
+{
+    if (N <= 0 || C <= 0 || H <= 0 || W <= 0 || stride <= 0) return -1;
+    const int Ho = scc_oracle_depthwise_out(H, stride), Wo = scc_oracle_depthwise_out(W, stride);
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int n = 0; n < N; ++n) {
+        for (int a = 0; a < C; ++a) {
+            const double *xi = x + ((size_t)n * C + a) * H * W;
+            const double *ka = kdw + (size_t)a * 9;
+            double *zo = z + ((size_t)n * C + a) * Ho * Wo;
+            for (int m = 0; m < Ho; ++m) {
+                for (int q = 0; q < Wo; ++q) {
+                    double acc = 0.0;
+                    for (int i = 0; i < 3; ++i) {
+                        for (int j = 0; j < 3; ++j) {
+                            int r = stride * m + i - 1, c = stride * q + j - 1;
+                            if (r < 0 || r >= H || c < 0 || c >= W) continue;
+                            acc += ka[i * 3 + j] * xi[(size_t)r * W + c];
+                        }
+                    }
+                    zo[(size_t)m * Wo + q] = acc;
+                }
+            }
+        }
+    }
     return 0;
 }

@@ -8,7 +8,7 @@ Arrays go in as NumPy arrays of any float dtype and are widened to float64
 before the C routines see them; results come back as float64.  Tensors are
 ``x[N, Cin, H, W]``, ``y/dy[N, Cout, H, W]``, ``w/dw[Cout, L]`` (Section 3.1 of the
 paper: each filter takes 1/cg of the input channels; Section 4.2 for the
-forward and backward definitions).
+forward and backward definitions), depthwise filters ``kdw[C, 3, 3]`` (Eq. 2).
 """
 import ctypes
 import os
@@ -43,6 +43,10 @@ def _load():
         for name in ("scc_oracle_forward", "scc_oracle_backward_input", "scc_oracle_backward_weight"):
             getattr(lib, name).argtypes = [dp, dp, dp] + [ctypes.c_int] * 5 + [ctypes.c_double]
             getattr(lib, name).restype = ctypes.c_int
+        lib.scc_oracle_depthwise_out.argtypes = [ctypes.c_int, ctypes.c_int]
+        lib.scc_oracle_depthwise_out.restype = ctypes.c_int
+        lib.scc_oracle_depthwise3x3.argtypes = [dp, dp, dp] + [ctypes.c_int] * 5
+        lib.scc_oracle_depthwise3x3.restype = ctypes.c_int
         _lib = lib
     return _lib
 
@@ -113,3 +117,26 @@ def backward_weight(x, dy, cg, co):
     dw = np.empty((Cout, L), dtype=np.float64)
     _check(_load().scc_oracle_backward_weight(_ptr(x), _ptr(dy), _ptr(dw), N, Cin, Cout, H * W, cg, float(co)))
     return dw
+
+
+def depthwise_out(size, stride):
+    """Rows (or columns) the depthwise stage produces from `size` rows at spatial stride `stride`."""
+    r = _load().scc_oracle_depthwise_out(int(size), int(stride))
+    if r < 0:
+        raise ValueError("not a depthwise stage: size=%r stride=%r" % (size, stride))
+    return r
+
+
+def depthwise3x3(x, kdw, stride=1):
+    """z[n,a,m,q] = sum_{i,j<3} kdw[a,i,j] * x[n,a,stride*m+i-1,stride*q+j-1], zero outside the map (Eq. 2)."""
+    x, kdw = _d(x), _d(kdw)
+    N, C, H, W = x.shape
+    assert kdw.shape == (C, 3, 3), "kdw must be [C, 3, 3]"
+    z = np.empty((N, C, depthwise_out(H, stride), depthwise_out(W, stride)), dtype=np.float64)
+    _check(_load().scc_oracle_depthwise3x3(_ptr(x), _ptr(kdw), _ptr(z), N, C, H, W, int(stride)))
+    return z
+
+
+def depthwise_scc_forward(x, kdw, w, cg, co, stride=1):
+    """The DW + SCC block's forward: the SCC forward of the depthwise stage's output (Section 3.1 on Eq. 2)."""
+    return forward(depthwise3x3(x, kdw, stride), w, cg, co)
