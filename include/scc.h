@@ -158,6 +158,39 @@ int scc_backward(const void* x, const void* dy, const void* w, void* dx, void* d
                  scc_dtype dtype, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Depthwise 3x3 stage of a DW + SCC block (Eq. 2 of the paper):
+ *     z[n,a,m,q] = sum_{i,j in 0..2} kdw[a,i,j] * x[n,a, s*m + i - 1, s*q + j - 1],   s = dw_stride,
+ * pixels outside the H x W map counting as zero (the filter is centred on input pixel (s*m, s*q), no
+ * flip).  The output map has scc_depthwise3x3_out(H, s) x scc_depthwise3x3_out(W, s) pixels,
+ * (size-1)/s + 1 each.  x: in, N*C*H*W.  kdw: in, C*9 values, [C][3][3] row-major, same dtype as x.
+ * z: out, N*C*Ho*Wo, same dtype.  Sums are binary32.  Errors: SCC_ERR_NULL, SCC_ERR_SHAPE (a dimension
+ * <= 0, dw_stride < 1, a map too large to index), SCC_ERR_DTYPE, SCC_ERR_LAUNCH.
+ */
+int scc_depthwise3x3_out(int size, int dw_stride);   /* rows (columns) produced, or SCC_ERR_SHAPE */
+int scc_depthwise3x3_forward(const void* x, const void* kdw, void* z,
+                             int N, int C, int H, int W, int dw_stride, scc_dtype dtype, void* stream);
+
+/*
+ * Forward of a whole DW + SCC block (Section 3.1: the SCC takes the place of the pointwise convolution
+ * behind the depthwise one of Eq. 2):
+ *     y = scc_forward(scc_depthwise3x3_forward(x, kdw), w)
+ * on the Ho x Wo map the depthwise stage produces.  x: in, N*Cin*H*W.  kdw: in, Cin*9.  w: in, Cout*L.
+ * y: out, N*Cout*Ho*Wo.  For fp32 layers with Cin a multiple of 16 and at most 1024 channels one kernel
+ * keeps the depthwise output of a tile of pixels for all channels on chip and feeds the SCC from there:
+ * x is read once, y written once, the intermediate never reaches memory (and is not rounded to the
+ * storage type).  Every other layer (bf16, other channel counts) runs the two stages one after the
+ * other through `workspace`, which then holds the depthwise output (N*Cin*Ho*Wo values of the dtype):
+ * at least scc_dw_forward_workspace_bytes(...) bytes, 256-byte aligned, owned by the caller, contents
+ * undefined afterwards; may be NULL when the query returns 0.
+ * Errors: as scc_forward and scc_depthwise3x3_forward, SCC_ERR_WORKSPACE.
+ */
+size_t scc_dw_forward_workspace_bytes(int N, int Cin, int Cout, int H, int W, int dw_stride,
+                                      int cg, double co, scc_dtype dtype);
+int scc_dw_forward(const void* x, const void* kdw, const void* w, void* y,
+                   int N, int Cin, int Cout, int H, int W, int dw_stride, int cg, double co,
+                   scc_dtype dtype, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * scc_backward_weight for callers that cannot allocate device memory or hand over a workspace:
  * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
  * arguments, kernels, arithmetic and summation order as scc_backward_weight (results are bitwise

@@ -210,6 +210,88 @@ int scc_backward(const void* x, const void* dy, const void* w, void* dx, void* d
     return scc_backward_weight(x, dy, dw, N, Cin, Cout, H, W, cg, co, dtype, workspace, workspace_bytes, stream);
 }
 
+// Geometry of the depthwise stage; SCC_ERR_SHAPE for a stride below 1 or maps too large for 32-bit pixel indices.
+static int make_dw_geom(int C, int H, int W, int dw_stride, scc::DwGeom* g)
+{
+    if (C <= 0 || H <= 0 || W <= 0 || dw_stride < 1) return SCC_ERR_SHAPE;
+    if ((long long)H * W * C > std::numeric_limits<int>::max()) return SCC_ERR_SHAPE;
+    g->H = H;
+    g->W = W;
+    g->s = dw_stride;
+    g->Ho = (H - 1) / dw_stride + 1;
+    g->Wo = (W - 1) / dw_stride + 1;
+    return SCC_OK;
+}
+
+int scc_depthwise3x3_out(int size, int dw_stride)
+{
+    if (size <= 0 || dw_stride < 1) return SCC_ERR_SHAPE;
+    return (size - 1) / dw_stride + 1;
+}
+
+int scc_depthwise3x3_forward(const void* x, const void* kdw, void* z, int N, int C, int H, int W, int dw_stride,
+                             scc_dtype dtype, void* stream)
+{
+    if (!x || !kdw || !z) return SCC_ERR_NULL;
+    scc::DwGeom g;
+    if (N <= 0) return SCC_ERR_SHAPE;
+    const int rc = make_dw_geom(C, H, W, dw_stride, &g);
+    if (rc != SCC_OK) return rc;
+    if ((long long)N * H * W > std::numeric_limits<int>::max()) return SCC_ERR_SHAPE;
+    if (!dtype_ok(dtype)) return SCC_ERR_DTYPE;
+    drop_stale_error();
+    if (dtype == SCC_F32)
+        return launch_status(
+            scc::launch_depthwise3x3((const float*)x, (const float*)kdw, (float*)z, N, C, g, (hipStream_t)stream));
+    return launch_status(scc::launch_depthwise3x3((const scc::bf16_t*)x, (const scc::bf16_t*)kdw, (scc::bf16_t*)z, N, C,
+                                                  g, (hipStream_t)stream));
+}
+
+// Problem of the SCC behind the depthwise stage (it sees the Ho x Wo map) and the stage's geometry.
+static int make_dw_problem(int N, int Cin, int Cout, int H, int W, int dw_stride, int cg, double co, Problem* p,
+                           scc::DwGeom* g)
+{
+    if (N <= 0) return SCC_ERR_SHAPE;
+    int rc = make_dw_geom(Cin, H, W, dw_stride, g);
+    if (rc != SCC_OK) return rc;
+    if ((long long)N * H * W > std::numeric_limits<int>::max()) return SCC_ERR_SHAPE;
+    return make_problem(N, Cin, Cout, g->Ho, g->Wo, cg, co, p);
+}
+
+size_t scc_dw_forward_workspace_bytes(int N, int Cin, int Cout, int H, int W, int dw_stride, int cg, double co,
+                                      scc_dtype dtype)
+{
+    Problem p;
+    scc::DwGeom g;
+    if (make_dw_problem(N, Cin, Cout, H, W, dw_stride, cg, co, &p, &g) != SCC_OK || !dtype_ok(dtype)) return 0;
+    if (dtype == SCC_F32 && scc::dw_forward_fused_eligible(p)) return 0;
+    return (size_t)p.NQ * Cin * (dtype == SCC_F32 ? 4 : 2);   // the depthwise stage's output
+}
+
+int scc_dw_forward(const void* x, const void* kdw, const void* w, void* y, int N, int Cin, int Cout, int H, int W,
+                   int dw_stride, int cg, double co, scc_dtype dtype, void* workspace, size_t workspace_bytes,
+                   void* stream)
+{
+    if (!x || !kdw || !w || !y) return SCC_ERR_NULL;
+    Problem p;
+    scc::DwGeom g;
+    const int rc = make_dw_problem(N, Cin, Cout, H, W, dw_stride, cg, co, &p, &g);
+    if (rc != SCC_OK) return rc;
+    if (!dtype_ok(dtype)) return SCC_ERR_DTYPE;
+    const size_t need = scc_dw_forward_workspace_bytes(N, Cin, Cout, H, W, dw_stride, cg, co, dtype);
+    if (need > 0 && (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 255u) != 0))
+        return SCC_ERR_WORKSPACE;
+    if (need == 0) {
+        drop_stale_error();
+        return launch_status(scc::launch_dw_forward_fused((const float*)x, (const float*)kdw, (const float*)w, (float*)y,
+                                                          p, g, (hipStream_t)stream));
+    }
+    // every other layer: the depthwise stage into the workspace, then the SCC forward on it
+    const int r1 = scc_depthwise3x3_forward(x, kdw, workspace, N, Cin, H, W, dw_stride, dtype, stream);
+    if (r1 != SCC_OK) return r1;
+    return scc_forward(workspace, w, y, N, Cin, Cout, g.Ho, g.Wo, cg, co, dtype, stream);
+}
+
 int scc_backward_weight_static(const void* x, const void* dy, void* dw, int N, int Cin, int Cout, int H, int W, int cg,
                                double co, scc_dtype dtype, void* stream)
 {

@@ -16,6 +16,12 @@ struct Problem {
     long long NQ; // N * HW: number of (sample, pixel) columns
 };
 
+// Geometry of the depthwise 3x3 stage in front of an SCC (Eq. 2): input map H x W, spatial stride s, output map
+// Ho x Wo with Ho = (H-1)/s + 1 (taps centred on input pixel (s*m, s*q), zero outside the map).
+struct DwGeom {
+    int H, W, Ho, Wo, s;
+};
+
 typedef uint16_t bf16_t;  // bfloat16 storage: the upper 16 bits of a binary32
 
 __device__ __forceinline__ float to_f32(float v) { return v; }
@@ -109,5 +115,12 @@ bool backward_fused_eligible(const Problem& p);
 size_t backward_fused_workspace(const Problem& p);  // bytes of K-split partials (0 when not split)
 hipError_t launch_backward_fused(const float* x, const float* dy, const float* w, float* dx, float* dw,
                                  float* workspace, const Problem& p, hipStream_t st);
+
+// Depthwise 3x3 stage and the fused DW + SCC forward (scc_dw_fwd.hip); `p` describes the SCC on the Ho x Wo map
+template <typename T>
+hipError_t launch_depthwise3x3(const T* x, const T* kdw, T* z, int N, int C, const DwGeom& g, hipStream_t st);
+bool dw_forward_fused_eligible(const Problem& p);
+hipError_t launch_dw_forward_fused(const float* x, const float* kdw, const float* w, float* y, const Problem& p,
+                                   const DwGeom& g, hipStream_t st);
 
 }  // namespace scc

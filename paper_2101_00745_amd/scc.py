@@ -17,6 +17,7 @@ SCC_F32, SCC_BF16 = 0, 1
 SYMBOLS = ("scc_window_params", "scc_forward", "scc_backward_input",
            "scc_backward_weight_workspace_bytes", "scc_backward_weight", "scc_backward_weight_static",
            "scc_backward_workspace_bytes", "scc_backward",
+           "scc_depthwise3x3_out", "scc_depthwise3x3_forward", "scc_dw_forward_workspace_bytes", "scc_dw_forward",
            "scc_status_string")
 STATIC_SCRATCH_BYTES = 8 << 20    # SCC_STATIC_SCRATCH_BYTES of include/scc.h
 
@@ -57,6 +58,15 @@ def load():
     lib.scc_backward.restype = c_int
     lib.scc_backward_weight_static.argtypes = [c_vp, c_vp, c_vp] + shape + [c_vp]
     lib.scc_backward_weight_static.restype = c_int
+    lib.scc_depthwise3x3_out.argtypes = [c_int, c_int]
+    lib.scc_depthwise3x3_out.restype = c_int
+    lib.scc_depthwise3x3_forward.argtypes = [c_vp, c_vp, c_vp] + [c_int] * 6 + [c_vp]
+    lib.scc_depthwise3x3_forward.restype = c_int
+    dw_shape = [c_int] * 7 + [c_dbl, c_int]     # N, Cin, Cout, H, W, dw_stride, cg, co, dtype
+    lib.scc_dw_forward_workspace_bytes.argtypes = dw_shape
+    lib.scc_dw_forward_workspace_bytes.restype = c_sz
+    lib.scc_dw_forward.argtypes = [c_vp] * 4 + dw_shape + [c_vp, c_sz, c_vp]
+    lib.scc_dw_forward.restype = c_int
     lib.scc_status_string.argtypes = [c_int]
     lib.scc_status_string.restype = ctypes.c_char_p
     _lib = lib
@@ -215,3 +225,59 @@ def scc_backward(x, dy, w, cg, co, out_dx=None, out_dw=None, workspace=None):
         _check(load().scc_backward(x.data_ptr(), dy.data_ptr(), w.data_ptr(), dx.data_ptr(), dw.data_ptr(), N, Cin, Cout,
                                    H, W, cg, float(co), code, ws_ptr, ws_len, _stream(dev)))
     return dx, dw
+
+
+def scc_depthwise3x3_out(size, dw_stride):
+    """Rows (columns) the depthwise 3x3 stage produces from `size` rows at spatial stride `dw_stride`."""
+    r = int(load().scc_depthwise3x3_out(int(size), int(dw_stride)))
+    _check(min(r, 0))
+    return r
+
+
+def scc_depthwise3x3_forward(x, kdw, dw_stride=1, out=None):
+    """z = DW3x3(x; kdw): x [N,C,H,W], kdw [C,3,3] -> z [N,C,Ho,Wo] (Eq. 2: centred taps, zero outside the map)."""
+    dev = _dev(x, kdw)
+    N, C, H, W = x.shape
+    if kdw.dtype != x.dtype or tuple(kdw.shape) != (C, 3, 3):
+        raise ValueError("kdw must be [C, 3, 3] with the dtype of x")
+    Ho, Wo = scc_depthwise3x3_out(H, dw_stride), scc_depthwise3x3_out(W, dw_stride)
+    z = torch.empty((N, C, Ho, Wo), dtype=x.dtype, device=dev) if out is None else out
+    if out is not None:
+        _dev(out)
+        assert out.shape == (N, C, Ho, Wo) and out.dtype == x.dtype
+    with torch.cuda.device(dev):
+        _check(load().scc_depthwise3x3_forward(x.data_ptr(), kdw.data_ptr(), z.data_ptr(), N, C, H, W, int(dw_stride),
+                                               _dtype_code(x), _stream(dev)))
+    return z
+
+
+def scc_dw_forward_workspace_bytes(N, Cin, Cout, H, W, dw_stride, cg, co, dtype=torch.float32):
+    code = SCC_F32 if dtype == torch.float32 else SCC_BF16
+    return int(load().scc_dw_forward_workspace_bytes(N, Cin, Cout, H, W, int(dw_stride), cg, float(co), code))
+
+
+def scc_dw_forward(x, kdw, w, cg, co, dw_stride=1, out=None, workspace=None):
+    """y = SCC(DW3x3(x; kdw); w), the forward of a DW + SCC block: x [N,Cin,H,W], kdw [Cin,3,3], w [Cout,Cin//cg]
+    -> y [N,Cout,Ho,Wo]."""
+    dev = _dev(x, kdw, w)
+    N, Cin, H, W = x.shape
+    Cout = w.shape[0]
+    if kdw.dtype != x.dtype or tuple(kdw.shape) != (Cin, 3, 3):
+        raise ValueError("kdw must be [Cin, 3, 3] with the dtype of x")
+    if w.dtype != x.dtype or w.dim() != 2 or (cg >= 1 and Cin % cg == 0 and w.shape[1] != Cin // cg):
+        raise ValueError("w must be [Cout, Cin//cg] with the dtype of x")
+    Ho, Wo = scc_depthwise3x3_out(H, dw_stride), scc_depthwise3x3_out(W, dw_stride)
+    code = _dtype_code(x)
+    need = int(load().scc_dw_forward_workspace_bytes(N, Cin, Cout, H, W, int(dw_stride), cg, float(co), code))
+    if workspace is None and need > 0:
+        workspace = torch.empty(need, dtype=torch.uint8, device=dev)
+    y = torch.empty((N, Cout, Ho, Wo), dtype=x.dtype, device=dev) if out is None else out
+    if out is not None:
+        _dev(out)
+        assert out.shape == (N, Cout, Ho, Wo) and out.dtype == x.dtype
+    ws_ptr = workspace.data_ptr() if workspace is not None else None
+    ws_len = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    with torch.cuda.device(dev):
+        _check(load().scc_dw_forward(x.data_ptr(), kdw.data_ptr(), w.data_ptr(), y.data_ptr(), N, Cin, Cout, H, W,
+                                     int(dw_stride), cg, float(co), code, ws_ptr, ws_len, _stream(dev)))
+    return y

@@ -8,7 +8,7 @@ the two sides see identical arrays.
 The shapes stand in for image-classification layers (CIFAR-10 / ImageNet sized
 feature maps, Section 5.1 of the paper); the datasets themselves are not used.
 Draws: numpy PCG64 (``default_rng``), float64 normal draws cast to float32.
-Seed = 745000 + 100*config + 10*layer + {0: x, 1: w, 2: dy}.
+Seed = 745000 + 100*config + 10*layer + {0: x, 1: w, 2: dy, 3: depthwise filters, 4: the block's input}.
 """
 import math
 from dataclasses import dataclass, replace
@@ -41,7 +41,7 @@ class Layer:
 
 
 def seed_of(layer, which):
-    return 745000 + 100 * layer.config + 10 * layer.layer + {"x": 0, "w": 1, "dy": 2}[which]
+    return 745000 + 100 * layer.config + 10 * layer.layer + {"x": 0, "w": 1, "dy": 2, "kdw": 3, "xin": 4}[which]
 
 
 def make_inputs(layer, seed_offset=0):
@@ -59,6 +59,24 @@ def make_inputs(layer, seed_offset=0):
     return (np.ascontiguousarray(x, dtype=np.float32),
             np.ascontiguousarray(w, dtype=np.float32),
             np.ascontiguousarray(dy, dtype=np.float32))
+
+
+def make_block_inputs(layer, dw_stride=1, seed_offset=0):
+    """(xin, kdw, w) for a DW + SCC block whose SCC stage is `layer`: the block's input map is the one a depthwise
+    3x3 stage of spatial stride `dw_stride` turns into the layer's H x W map (H*stride x W*stride pixels),
+    depthwise filters ~ N(0, 1/3) (nine taps: unit output variance), w as in make_inputs."""
+    def draw(which, shape):
+        rng = np.random.default_rng(seed_of(layer, which) + 1000003 * seed_offset)
+        return rng.standard_normal(shape)
+
+    xin = draw("xin", (layer.N, layer.Cin, layer.H * dw_stride, layer.W * dw_stride))
+    if layer.x_law == "halfnormal":
+        xin = np.abs(xin)
+    kdw = draw("kdw", (layer.Cin, 3, 3)) / 3.0
+    std = layer.w_std if layer.w_std > 0 else math.sqrt(2.0 / layer.L)
+    w = draw("w", (layer.Cout, layer.L)) * std
+    return (np.ascontiguousarray(xin, dtype=np.float32), np.ascontiguousarray(kdw, dtype=np.float32),
+            np.ascontiguousarray(w, dtype=np.float32))
 
 
 # configs[0]: the small case the oracle finishes instantly.
@@ -87,6 +105,8 @@ STACK = [Layer("c5_l%02d_%dto%d_%dx%d" % (i, ci, co_, s, s), 5, N=128, Cin=ci, C
                cg=2, co=0.5, layer=i) for i, (ci, co_, s) in enumerate(_STACK_SHAPES)]
 
 ALL_FULL = METRIC_SWEEP + [LATE, EXPAND] + STACK
+# spatial stride of the depthwise stage in front of each stack layer: 2 where the map halves (MobileNet shape)
+STACK_DW_STRIDE = [1 if i == 0 or _STACK_SHAPES[i][2] == _STACK_SHAPES[i - 1][2] else 2 for i in range(len(_STACK_SHAPES))]
 
 # The paper's other sweeps on the metric layer (Section 5.3): the number of channel groups cg in
 # {1, 2, 4, 8} at 50% overlap, and the batch size from inference-sized 16 up to 1024.
@@ -105,3 +125,9 @@ def algorithmic_bytes(layer, elem_bytes=4):
 def algorithmic_flops(layer):
     """2 * MACs of one pass: only the banded work, never the dense Cin*Cout product."""
     return 2 * layer.N * layer.Cout * layer.L * layer.HW
+
+
+def block_algorithmic_bytes(layer, dw_stride=1, elem_bytes=4):
+    """Bytes the forward of a DW + SCC block must move: its input, its output and both sets of weights, once."""
+    return elem_bytes * (layer.N * layer.Cin * layer.HW * dw_stride * dw_stride + layer.N * layer.Cout * layer.HW +
+                         layer.Cout * layer.L + 9 * layer.Cin)

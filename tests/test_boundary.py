@@ -17,7 +17,7 @@ FAKE = ctypes.c_void_p(0x1000)  # non-NULL, never dereferenced: every call below
 def declared_functions():
     text = open(os.path.join(ROOT, "include", "scc.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(scc_[a-z_]+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(scc_[a-z0-9_]+)\s*\(", text)))
 
 
 def test_library_exports_every_declared_symbol():
@@ -36,16 +36,9 @@ def test_status_strings():
 
 
 def alg1_period(Cin, Cout, cg, co):
+    """Distinct window starts among the first Cout filters (Algorithm 1: filter k starts k * (gw - ov) channels on, folded)."""
     gw = Cin // cg
-    seen, sv, ev = [], 0, gw
-    for _ in range(Cout):
-        st = sv % Cin
-        if st in seen:
-            break
-        seen.append(st)
-        sv = ev - int(co * gw)
-        ev = sv + gw
-    return len(seen)
+    return len({(k * (gw - int(co * gw))) % Cin for k in range(Cout)})
 
 
 @pytest.mark.parametrize("Cin,Cout,cg,co", [(4, 4, 2, 0.5), (256, 256, 4, 0.0), (256, 256, 4, 0.25), (256, 256, 4, 0.5),
@@ -117,6 +110,49 @@ def test_null_pointers_are_rejected():
         ptrs = [FAKE] * 5
         ptrs[i] = None
         assert lib.scc_backward(*ptrs, *shape, None, 0, None) == -1
+
+
+DW_BAD = [
+    (dict(N=0), -2), (dict(Cin=-4), -2), (dict(Cout=0), -2), (dict(H=0), -2), (dict(W=-1), -2), (dict(cg=0), -2),
+    (dict(cg=3), -2), (dict(s=0), -2), (dict(s=-2), -2), (dict(co=-0.01), -3), (dict(co=math.nan), -3),
+    (dict(dtype=2), -4), (dict(N=1 << 20, H=1 << 10, W=1 << 10), -2),
+]
+
+
+@pytest.mark.parametrize("over,code", DW_BAD)
+def test_dw_block_invalid_arguments_are_rejected_on_the_host(over, code):
+    a = dict(N=2, Cin=8, Cout=6, H=5, W=5, s=1, cg=2, co=0.5, dtype=0)
+    a.update(over)
+    lib = S.load()
+    shape = (a["N"], a["Cin"], a["Cout"], a["H"], a["W"], a["s"], a["cg"], a["co"], a["dtype"])
+    assert lib.scc_dw_forward(FAKE, FAKE, FAKE, FAKE, *shape, FAKE, 1 << 30, None) == code
+    assert lib.scc_dw_forward_workspace_bytes(*shape) == 0
+    if not ({"Cout", "cg", "co"} & set(over)):
+        assert lib.scc_depthwise3x3_forward(FAKE, FAKE, FAKE, a["N"], a["Cin"], a["H"], a["W"], a["s"], a["dtype"],
+                                            None) == code
+
+
+def test_dw_block_null_pointers_and_workspace():
+    lib = S.load()
+    shape = (2, 8, 6, 5, 5, 2, 2, 0.5, 0)       # Cin = 8 is not a multiple of 16: the two-stage path, needs a workspace
+    need = lib.scc_dw_forward_workspace_bytes(*shape)
+    assert need == 2 * 8 * 3 * 3 * 4            # the depthwise output: N x Cin x 3 x 3 binary32 values
+    for i in range(4):
+        ptrs = [FAKE] * 4
+        ptrs[i] = None
+        assert lib.scc_dw_forward(*ptrs, *shape, FAKE, need, None) == -1
+    assert lib.scc_dw_forward(FAKE, FAKE, FAKE, FAKE, *shape, None, 0, None) == -5
+    assert lib.scc_dw_forward(FAKE, FAKE, FAKE, FAKE, *shape, FAKE, need - 1, None) == -5
+    assert lib.scc_dw_forward(FAKE, FAKE, FAKE, FAKE, *shape, ctypes.c_void_p(0x1010), need, None) == -5   # misaligned
+    for i in range(3):
+        ptrs = [FAKE] * 3
+        ptrs[i] = None
+        assert lib.scc_depthwise3x3_forward(*ptrs, 2, 8, 5, 5, 1, 0, None) == -1
+    # layers the fused kernel takes need no workspace
+    assert lib.scc_dw_forward_workspace_bytes(128, 256, 256, 16, 16, 1, 4, 0.5, 0) == 0
+    assert lib.scc_dw_forward_workspace_bytes(128, 256, 256, 16, 16, 1, 4, 0.5, 1) == 128 * 256 * 256 * 2   # bf16
+    assert lib.scc_depthwise3x3_out(32, 2) == 16 and lib.scc_depthwise3x3_out(7, 2) == 4
+    assert lib.scc_depthwise3x3_out(0, 1) == -2 and lib.scc_depthwise3x3_out(5, 0) == -2
 
 
 def test_backward_workspace_is_checked_on_the_host():
