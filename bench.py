@@ -282,12 +282,57 @@ def sweep(S, Wk, torch, steps, warmup, path):
     summary = {"stack_us_three_passes": round(sum(r["us_three_passes"] for r in stack), 1),
                "stack_us_fwd_plus_backward": round(sum(r["us_fwd_plus_backward"] for r in stack), 1),
                "stack_bound_us_sum": round(3 * sum(r["bound_us_per_pass"] for r in stack), 1)}
+    blocks = block_sweep(S, Wk, torch)
     os.makedirs(os.path.dirname(os.path.abspath(path)), exist_ok=True)
     with open(path, "w") as f:
-        json.dump({"rows": rows, "summary": summary}, f, indent=1)
+        json.dump({"rows": rows, "summary": summary, "dw_scc_blocks": blocks}, f, indent=1)
     print("stack of 13 layers: %.1f us as three passes, %.1f us as forward + scc_backward (bound %.1f us)" %
           (summary["stack_us_three_passes"], summary["stack_us_fwd_plus_backward"], summary["stack_bound_us_sum"]),
           file=sys.stderr, flush=True)
+
+
+def block_sweep(S, Wk, torch, replays_floor=MIN_REPLAYS):
+    """Forward of the DW + SCC block (depthwise 3x3 stage in front of the SCC; stride 2 where the stack's map halves)
+    on the metric layer and the 13 stack layers, fp32: the call as the library dispatches it (`auto`), the fused
+    kernel forced, and the two stages run one after the other, each on cold rotating buffers."""
+    dev = torch.device("cuda:0")
+    out = []
+    for layer, s in [(Wk.METRIC, 1)] + list(zip(Wk.STACK, Wk.STACK_DW_STRIDE)):
+        xin, kdw, w = Wk.make_block_inputs(layer, s)
+        out_bytes = 4 * layer.N * layer.Cout * layer.HW
+        R = max(2, min(256, -(-ROTATE_BYTES // max(xin.nbytes, out_bytes))))
+        sets = [dict(x=torch.from_numpy(xin).to(dev).roll(r, 0).contiguous(), k=torch.from_numpy(kdw).to(dev),
+                     w=torch.from_numpy(w).to(dev),
+                     y=torch.empty((layer.N, layer.Cout, layer.H, layer.W), device=dev)) for r in range(R)]
+        shape = (layer.N, layer.Cin, layer.Cout, xin.shape[2], xin.shape[3], s, layer.cg, layer.co)
+        ws = torch.empty(max(256, S.scc_dw_forward_workspace_bytes(*shape), 4 * layer.N * layer.Cin * layer.HW),
+                         dtype=torch.uint8, device=dev)
+        z = ws.view(torch.float32)[:layer.N * layer.Cin * layer.HW].view(layer.N, layer.Cin, layer.H, layer.W)
+
+        def auto(b):
+            S.scc_dw_forward(b["x"], b["k"], b["w"], layer.cg, layer.co, s, out=b["y"], workspace=ws)
+
+        def fused(b):
+            S.scc_dw_forward(b["x"], b["k"], b["w"], layer.cg, layer.co, s, out=b["y"], fused=True)
+
+        def two(b):
+            S.scc_depthwise3x3_forward(b["x"], b["k"], s, out=z)
+            S.scc_forward(z, b["w"], layer.cg, layer.co, out=b["y"])
+
+        timer = Timer(torch, sets, False)
+        reps = max(replays_floor, -(-96 // R))
+        us = {name: timer.time(fn, reps, 2)[2] * 1e3 for name, fn in (("auto", auto), ("fused", fused), ("two_stages", two))}
+        alg = Wk.block_algorithmic_bytes(layer, s)
+        out.append({"layer": layer.name, "dw_stride": s, "MB": round(alg / 1e6, 2), "bound_us": round(alg / (HBM_PEAK_GBS * 1e3), 2),
+                    "library_fuses": S.scc_dw_forward_workspace_bytes(*shape) == 0,
+                    "us": {k: round(v, 2) for k, v in us.items()}, "GBs_auto": round(alg / us["auto"] / 1e3, 1)})
+        print("block %-30s s=%d %6.1f MB | auto %7.1f (%s) fused %7.1f two stages %7.1f us | bound %5.1f us" %
+              (layer.name, s, alg / 1e6, us["auto"], "fused" if out[-1]["library_fuses"] else "two stages", us["fused"],
+               us["two_stages"], out[-1]["bound_us"]), file=sys.stderr, flush=True)
+        del sets, ws, z
+    print("DW + SCC forward over the 13 stack layers: %.1f us as dispatched, %.1f us in two stages everywhere" %
+          (sum(r["us"]["auto"] for r in out[1:]), sum(r["us"]["two_stages"] for r in out[1:])), file=sys.stderr, flush=True)
+    return out
 
 
 def all_cases(Wk, torch):

@@ -175,17 +175,25 @@ int scc_depthwise3x3_forward(const void* x, const void* kdw, void* z,
  * behind the depthwise one of Eq. 2):
  *     y = scc_forward(scc_depthwise3x3_forward(x, kdw), w)
  * on the Ho x Wo map the depthwise stage produces.  x: in, N*Cin*H*W.  kdw: in, Cin*9.  w: in, Cout*L.
- * y: out, N*Cout*Ho*Wo.  For fp32 layers with Cin a multiple of 16 and at most 1024 channels one kernel
- * keeps the depthwise output of a tile of pixels for all channels on chip and feeds the SCC from there:
- * x is read once, y written once, the intermediate never reaches memory (and is not rounded to the
- * storage type).  Every other layer (bf16, other channel counts) runs the two stages one after the
- * other through `workspace`, which then holds the depthwise output (N*Cin*Ho*Wo values of the dtype):
- * at least scc_dw_forward_workspace_bytes(...) bytes, 256-byte aligned, owned by the caller, contents
- * undefined afterwards; may be NULL when the query returns 0.
+ * y: out, N*Cout*Ho*Wo.
+ * Two paths.  Fused (fp32 layers with Cin a multiple of 16 and at most 1104 channels): one kernel keeps the
+ * depthwise output of a tile of pixels for all channels on chip and feeds the SCC from there; x is read
+ * once, y written once, the intermediate never reaches memory (and is not rounded to the storage type).
+ * Two stages (every layer): scc_depthwise3x3_forward into `workspace`, then scc_forward on it; `workspace`
+ * then holds the depthwise output (N*Cin*Ho*Wo values of the dtype).
+ * scc_dw_forward_workspace_bytes(...) returns 0 for the layers the library runs fused by its own choice
+ * (fusable and at least 16384 output pixels over the batch, where fusing is the faster path) and the size
+ * of the depthwise output for all others.  A call with a workspace of at least that size (256-byte aligned,
+ * owned by the caller, contents undefined afterwards) takes the path the library prefers.  A call with
+ * workspace == NULL runs fused whenever scc_dw_forward_fusable(...) returns 1, also where two stages would
+ * be faster, and is refused with SCC_ERR_WORKSPACE otherwise.
+ * scc_dw_forward_fusable: 1 or 0, or a negative scc_status for invalid arguments.
  * Errors: as scc_forward and scc_depthwise3x3_forward, SCC_ERR_WORKSPACE.
  */
 size_t scc_dw_forward_workspace_bytes(int N, int Cin, int Cout, int H, int W, int dw_stride,
                                       int cg, double co, scc_dtype dtype);
+int scc_dw_forward_fusable(int N, int Cin, int Cout, int H, int W, int dw_stride,
+                           int cg, double co, scc_dtype dtype);
 int scc_dw_forward(const void* x, const void* kdw, const void* w, void* y,
                    int N, int Cin, int Cout, int H, int W, int dw_stride, int cg, double co,
                    scc_dtype dtype, void* workspace, size_t workspace_bytes, void* stream);

@@ -264,8 +264,18 @@ size_t scc_dw_forward_workspace_bytes(int N, int Cin, int Cout, int H, int W, in
     Problem p;
     scc::DwGeom g;
     if (make_dw_problem(N, Cin, Cout, H, W, dw_stride, cg, co, &p, &g) != SCC_OK || !dtype_ok(dtype)) return 0;
-    if (dtype == SCC_F32 && scc::dw_forward_fused_eligible(p)) return 0;
+    if (dtype == SCC_F32 && scc::dw_forward_fused_preferred(p)) return 0;
     return (size_t)p.NQ * Cin * (dtype == SCC_F32 ? 4 : 2);   // the depthwise stage's output
+}
+
+int scc_dw_forward_fusable(int N, int Cin, int Cout, int H, int W, int dw_stride, int cg, double co, scc_dtype dtype)
+{
+    Problem p;
+    scc::DwGeom g;
+    const int rc = make_dw_problem(N, Cin, Cout, H, W, dw_stride, cg, co, &p, &g);
+    if (rc != SCC_OK) return rc;
+    if (!dtype_ok(dtype)) return SCC_ERR_DTYPE;
+    return dtype == SCC_F32 && scc::dw_forward_fused_eligible(p) ? 1 : 0;
 }
 
 int scc_dw_forward(const void* x, const void* kdw, const void* w, void* y, int N, int Cin, int Cout, int H, int W,
@@ -279,9 +289,11 @@ int scc_dw_forward(const void* x, const void* kdw, const void* w, void* y, int N
     if (rc != SCC_OK) return rc;
     if (!dtype_ok(dtype)) return SCC_ERR_DTYPE;
     const size_t need = scc_dw_forward_workspace_bytes(N, Cin, Cout, H, W, dw_stride, cg, co, dtype);
-    if (need > 0 && (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 255u) != 0))
+    // without a workspace the fused kernel runs wherever it can, also where the two stages would be faster
+    const bool fused = dtype == SCC_F32 && (need == 0 || (!workspace && scc::dw_forward_fused_eligible(p)));
+    if (!fused && (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 255u) != 0))
         return SCC_ERR_WORKSPACE;
-    if (need == 0) {
+    if (fused) {
         drop_stale_error();
         return launch_status(scc::launch_dw_forward_fused((const float*)x, (const float*)kdw, (const float*)w, (float*)y,
                                                           p, g, (hipStream_t)stream));

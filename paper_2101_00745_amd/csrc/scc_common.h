@@ -119,7 +119,8 @@ hipError_t launch_backward_fused(const float* x, const float* dy, const float* w
 // Depthwise 3x3 stage and the fused DW + SCC forward (scc_dw_fwd.hip); `p` describes the SCC on the Ho x Wo map
 template <typename T>
 hipError_t launch_depthwise3x3(const T* x, const T* kdw, T* z, int N, int C, const DwGeom& g, hipStream_t st);
-bool dw_forward_fused_eligible(const Problem& p);
+bool dw_forward_fused_eligible(const Problem& p);    // the fused kernel can run the layer
+bool dw_forward_fused_preferred(const Problem& p);   // ... and is the faster path for it
 hipError_t launch_dw_forward_fused(const float* x, const float* kdw, const float* w, float* y, const Problem& p,
                                    const DwGeom& g, hipStream_t st);
 

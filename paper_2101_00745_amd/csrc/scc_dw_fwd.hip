@@ -27,6 +27,8 @@ struct DwTiling {
     int U;          // channels a tile spans: L + g * (TM - 1)
     long long nct;  // column tiles
     long long chunk;  // consecutive column tiles given to one XCD: ceil(nct / 8)
+    int al4;        // g and L are multiples of 4 and w is 16-byte aligned: a lane's groups of four weights are wholly
+                    // inside or outside a window and are read with 16-byte loads
 };
 
 int pow2_floor_dw(int v)
@@ -37,79 +39,152 @@ int pow2_floor_dw(int v)
 }
 
 // ---------------------------------------------------------------------------------------------------------
-// Stand-alone depthwise stage: one thread per output value (VEC: per 4 consecutive values of one output row,
-// for spatial stride 1 and rows that are a multiple of 4 pixels).  Sums are binary32, taps in row-major order.
-template <typename T_, bool VEC>
+// A strip: RB consecutive output rows x 4 consecutive output columns of one channel, for spatial stride S (1 or 2).
+// It reads NR = S*(RB-1)+3 input rows, each once: 4*S pixels from the strip's first input column on (one or two
+// 16-byte loads for binary32).  The pixel left of them and, for S == 1, the pixel right of them are the last and
+// first pixel of what the NEIGHBOURING LANES loaded for the same row: lane l-1 must own the strip to the left and
+// lane l+1 the strip to the right (same channel, same rows) whenever `left` / `right` is set and `lo` / `hi` is
+// not; they are fetched with a lane shuffle (single misaligned 4-byte loads measured 40 % of the whole stage).
+//   xc       input pixel (S*r0, S*cw) of the channel: centre of the strip's first output
+//   W        pixels per input row
+//   rowmask  bit t set: input row S*r0 - 1 + t lies inside the map (bit 1 always is)
+//   left     the input column left of the strip exists; right (S == 1): the column right of it exists
+//   lo, hi   the lane has no lane below / above it in the wavefront that owns the neighbouring strip: it loads
+//            the edge pixel itself
+// Rows and columns outside the map are read at an address inside it and replaced by zero.  Every lane of the
+// wavefront must call this together (the shuffles are wavefront-wide).
+template <int S, int RB, typename T_>
+__device__ __forceinline__ void dw_strip(const T_* xc, int W, const float (&k)[9], uint32_t rowmask, bool left, bool right,
+                                         bool lo, bool hi, float (&out)[RB][4])
+{
+    typedef T_ tvec __attribute__((ext_vector_type(4)));
+    constexpr int NR = S * (RB - 1) + 3;
+#pragma unroll
+    for (int rr = 0; rr < RB; ++rr)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) out[rr][i] = 0.f;
+#pragma unroll
+    for (int t = 0; t < NR; ++t) {
+        const bool ok = (rowmask >> t) & 1u;
+        const T_* row = ok ? xc + (t - 1) * W : xc;
+        float v[4 * S + 2];
+        float raw[4 * S];
+#pragma unroll
+        for (int h = 0; h < S; ++h) {
+            const tvec m = *(const tvec*)(row + 4 * h);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) raw[4 * h + e] = to_f32(m[e]);
+        }
+        float lv = __shfl_up(raw[4 * S - 1], 1, 64);
+        if (lo && left) lv = to_f32(row[-1]);
+        v[0] = (ok && left) ? lv : 0.f;
+#pragma unroll
+        for (int e = 0; e < 4 * S; ++e) v[1 + e] = ok ? raw[e] : 0.f;
+        if constexpr (S == 1) {
+            float rv = __shfl_down(raw[0], 1, 64);
+            if (hi && right) rv = to_f32(row[4]);
+            v[5] = (ok && right) ? rv : 0.f;
+        } else {
+            v[4 * S + 1] = 0.f;   // never used: the last tap of the last output reads v[S*3 + 2] = v[8]
+        }
+#pragma unroll
+        for (int rr = 0; rr < RB; ++rr) {
+            const int di = t - S * rr;   // tap row of output row rr that this input row feeds
+            if (di < 0 || di > 2) continue;
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 3; ++j) out[rr][i] += k[di * 3 + j] * v[S * i + j];
+        }
+    }
+}
+
+// Stand-alone depthwise stage on strips (see dw_strip): stride 1 or 2 with output rows that are a multiple of 4
+// pixels, input maps of exactly S times the output size, RB dividing the output rows, tensors aligned to 4 values.
+template <typename T_, int S, int RB>
+__global__ __launch_bounds__(256) void depthwise3x3_strips(const T_* __restrict__ x, const T_* __restrict__ kdw,
+                                                           T_* __restrict__ z, int C, DwGeom G, long long items)
+{
+    typedef T_ tvec __attribute__((ext_vector_type(4)));
+    const size_t HWi = (size_t)G.H * G.W, HWo = (size_t)G.Ho * G.Wo;
+    const uint32_t W4 = G.Wo / 4, SB = G.Ho / RB;
+    // 32-bit index arithmetic (the launcher sends fewer than 2^31 strips here): 64-bit divisions in every lane
+    // cost more than the stencil itself.  All lanes of a wavefront run the same number of trips (the strip
+    // routine shuffles between lanes); lanes past the end compute strip 0 again and store nothing.
+    const uint32_t lane = threadIdx.x & 63;
+    for (uint32_t e0 = blockIdx.x * 256u; e0 < (uint32_t)items; e0 += gridDim.x * 256u) {
+        const uint32_t ee = e0 + threadIdx.x;
+        const bool live = ee < (uint32_t)items;
+        const uint32_t e = live ? ee : 0;
+        const int cw = (int)(e % W4) * 4;
+        uint32_t t = e / W4;
+        const int r0 = (int)(t % SB) * RB;
+        t /= SB;                          // t = n*C + a
+        const int a = (int)(t % (uint32_t)C);
+        float k[9];
+#pragma unroll
+        for (int i = 0; i < 9; ++i) k[i] = to_f32(kdw[a * 9 + i]);
+        uint32_t rowmask = (1u << (S * (RB - 1) + 3)) - 1;
+        if (r0 == 0) rowmask &= ~1u;
+        if (S == 1 && r0 + RB == G.Ho) rowmask &= ~(1u << (RB + 1));
+        float out[RB][4];
+        // consecutive strips of a row are consecutive lanes; the first and last lane of the wavefront and the
+        // last live one have no neighbour to ask
+        dw_strip<S, RB>(x + t * HWi + (size_t)(S * r0) * G.W + S * cw, G.W, k, rowmask, cw > 0, cw + 4 < G.Wo, lane == 0,
+                        lane == 63 || ee + 1 >= (uint32_t)items, out);
+        if (!live) continue;
+        T_* zo = z + t * HWo + (size_t)r0 * G.Wo + cw;
+#pragma unroll
+        for (int rr = 0; rr < RB; ++rr) {
+            tvec o;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) o[i] = from_f32<T_>(out[rr][i]);
+            __builtin_nontemporal_store(o, (tvec*)(zo + rr * G.Wo));
+        }
+    }
+}
+
+// Stand-alone depthwise stage, any stride and map size: one thread per output value, taps in row-major order.
+template <typename T_>
 __global__ __launch_bounds__(256) void depthwise3x3_kernel(const T_* __restrict__ x, const T_* __restrict__ kdw,
                                                            T_* __restrict__ z, int C, DwGeom G, long long items)
 {
-    const long long HWi = (long long)G.H * G.W, HWo = (long long)G.Ho * G.Wo;
+    const long long HWi = (long long)G.H * G.W;
     for (long long e = (long long)blockIdx.x * 256 + threadIdx.x; e < items; e += (long long)gridDim.x * 256) {
-        if constexpr (VEC) {
-            const int W4 = G.Wo / 4;
-            const int cw = (int)(e % W4) * 4;
-            long long t = e / W4;
-            const int r = (int)(t % G.Ho);
-            t /= G.Ho;                       // t = n*C + a
-            const int a = (int)(t % C);
-            const T_* xc = x + t * HWi + (long long)r * G.W + cw;
-            float k[9];
+        const int q = (int)(e % G.Wo);
+        long long t = e / G.Wo;
+        const int m = (int)(t % G.Ho);
+        t /= G.Ho;
+        const int a = (int)(t % C);
+        const T_* xc = x + t * HWi;
+        float out = 0.f;
 #pragma unroll
-            for (int i = 0; i < 9; ++i) k[i] = to_f32(kdw[a * 9 + i]);
-            float out[4] = {0.f, 0.f, 0.f, 0.f};
+        for (int i = 0; i < 3; ++i) {
+            const int rr = G.s * m + i - 1;
+            if (rr < 0 || rr >= G.H) continue;
 #pragma unroll
-            for (int dr = -1; dr <= 1; ++dr) {
-                const int rr = r + dr;
-                if (rr < 0 || rr >= G.H) continue;
-                const T_* row = xc + dr * G.W;
-                float v[6];
-                v[0] = cw > 0 ? to_f32(row[-1]) : 0.f;
-#pragma unroll
-                for (int i = 0; i < 4; ++i) v[1 + i] = to_f32(row[i]);
-                v[5] = cw + 4 < G.W ? to_f32(row[4]) : 0.f;
-#pragma unroll
-                for (int i = 0; i < 4; ++i)
-#pragma unroll
-                    for (int j = 0; j < 3; ++j) out[i] += k[(dr + 1) * 3 + j] * v[i + j];
+            for (int j = 0; j < 3; ++j) {
+                const int cc = G.s * q + j - 1;
+                if (cc < 0 || cc >= G.W) continue;
+                out += to_f32(kdw[a * 9 + i * 3 + j]) * to_f32(xc[(long long)rr * G.W + cc]);
             }
-            T_* zo = z + t * HWo + (long long)r * G.Wo + cw;
-#pragma unroll
-            for (int i = 0; i < 4; ++i) zo[i] = from_f32<T_>(out[i]);
-        } else {
-            const int q = (int)(e % G.Wo);
-            long long t = e / G.Wo;
-            const int m = (int)(t % G.Ho);
-            t /= G.Ho;
-            const int a = (int)(t % C);
-            const T_* xc = x + t * HWi;
-            float out = 0.f;
-#pragma unroll
-            for (int i = 0; i < 3; ++i) {
-                const int rr = G.s * m + i - 1;
-                if (rr < 0 || rr >= G.H) continue;
-#pragma unroll
-                for (int j = 0; j < 3; ++j) {
-                    const int cc = G.s * q + j - 1;
-                    if (cc < 0 || cc >= G.W) continue;
-                    out += to_f32(kdw[a * 9 + i * 3 + j]) * to_f32(xc[(long long)rr * G.W + cc]);
-                }
-            }
-            z[e] = from_f32<T_>(out);
         }
+        z[e] = from_f32<T_>(out);
     }
 }
 
 // ---------------------------------------------------------------------------------------------------------
 // Fused DW + SCC forward, fp32.
 //   CP    column groups of 32 per workgroup (the LDS tile is Cin x 32*CP binary32 values)
-//   AL4   g and L are multiples of 4: groups of four weights are wholly inside or outside a window and 16-byte
-//         aligned, so the A operand is read with 16-byte loads
-//   FAST  spatial stride 1, rows that are a multiple of 4 pixels, x aligned to 16 bytes: a thread's 4 columns
-//         are 4 consecutive pixels of one row and each row of the stencil is one 16-byte load plus two edge values
+//   S,RB  phase 1 on strips (dw_strip): spatial stride S (1 or 2), RB output rows per strip; the tile is then whole
+//         output rows (32*CP is a multiple of the row length) cut into strips that do not straddle samples.
+//         S == 0: any stride and map size, every thread computes its 4 columns tap by tap.
 //
-// LDS layout: zl[c / 4][column][c % 4] (16 bytes per (channel quad, column)): a lane of phase 2 reads the 8
-// channels of its half of a 16-channel chunk at its column with two 16-byte reads, 16 lanes covering all banks.
-template <int CP, bool AL4, bool FAST>
+// LDS layout: zl[c / 4][column][c % 4] (16 bytes per (channel quad, column)), a quad's row padded by one column:
+// a lane of phase 2 reads the 8 channels of its half of a 16-channel chunk at its column with two 16-byte reads
+// (16 lanes cover all banks), and the writes of phase 1 (lanes differ in channel and column group) spread over
+// all banks too.
+template <int CP, int S, int RB>
 __global__ __launch_bounds__(256) void dw_scc_forward_lds(const float* __restrict__ x, const float* __restrict__ kdw,
                                                           const float* __restrict__ w, float* __restrict__ y, Problem P,
                                                           DwGeom G, DwTiling T)
@@ -117,8 +192,7 @@ __global__ __launch_bounds__(256) void dw_scc_forward_lds(const float* __restric
     extern __shared__ __align__(16) unsigned char lds_raw[];
     float* zl = (float*)lds_raw;
     constexpr int TP = 32 * CP;
-    constexpr int G4 = TP / 4;           // groups of 4 columns per tile
-    constexpr int CSTEP = 256 / G4;      // channels the workgroup covers per trip of phase 1
+    constexpr int TPP = TP + 1;          // padded row of a channel quad, in columns
 
     // workgroup -> column tile; blockIdx % 8 names the XCD, and every XCD takes a contiguous run of column
     // tiles, so the rows of x that neighbouring tiles of one sample both need meet in one L2
@@ -128,95 +202,151 @@ __global__ __launch_bounds__(256) void dw_scc_forward_lds(const float* __restric
     const int tid = threadIdx.x;
     const int HWi = G.H * G.W;
 
+    // ---------------- phase 2's A operand is requested one step ahead of its use; the first step's before phase 1
+    // A step is one chunk of a filter tile: the 16 channels one matrix instruction contracts.
+    const int lane = tid & 63, wave = tid >> 6, col = lane & 31, kg = lane >> 5;
+    const Band& b = T.b;
+    struct Step {
+        int ft, cb;        // filter tile and first channel (unwrapped axis) of the block; ft >= ntiles: past the end
+        int cend;          // one past the tile's span
+        int sf;            // window start of this lane's filter
+        long long kf;      // this lane's filter (A row lane & 31 of the tile), -1 if the tile has none there
+    };
+    auto tile_of = [&](int ft) {
+        Step st;
+        st.ft = ft;
+        const int ib = ft % T.IB, mb = ft / T.IB;
+        const int f = lane & 31;
+        const int m = mb * T.TM + f / T.TI, i = ib * T.TI + f % T.TI;
+        st.kf = -1;
+        if (ft < T.ntiles && m < b.P) {
+            st.kf = (long long)(((long long)m * b.inv) % b.P) + (long long)b.P * i;
+            if (st.kf >= P.Cout) st.kf = -1;
+        }
+        st.sf = b.g * m;
+        const int c0 = b.g * mb * T.TM;     // window start of the tile's first filter column
+        st.cb = c0 & ~15;
+        st.cend = c0 + T.U;
+        return st;
+    };
+    auto next_of = [&](const Step& st) {
+        if (st.cb + 16 < st.cend) {
+            Step n = st;
+            n.cb += 16;
+            return n;
+        }
+        return tile_of(st.ft + 4);
+    };
+    // the lane's 8 weights of the chunk, zero outside the filter's window
+    auto load_a = [&](const Step& st, float (&a)[8]) {
+        const float* wrow = w + (st.kf >= 0 ? st.kf : 0) * P.L;
+        {
+            const int j0 = st.cb + 8 * kg - st.sf;   // weight index of the lane's first channel
+            if (T.al4) {      // uniform over the grid
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    const int j = j0 + 4 * h;
+                    const bool in = st.kf >= 0 && j >= 0 && j < P.L;
+                    const f32x4 v = *(const f32x4*)(wrow + (in ? j : 0));
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) a[4 * h + e] = in ? v[e] : 0.f;
+                }
+            } else {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const int j = j0 + e;
+                    const bool in = st.kf >= 0 && j >= 0 && j < P.L;
+                    const float v = wrow[in ? j : 0];
+                    a[e] = in ? v : 0.f;
+                }
+            }
+        }
+    };
+    Step cur = tile_of(wave);
+    float araw[8];
+    load_a(cur, araw);
+
     // ---------------- phase 1: z of all channels for this tile's columns
-    {
+    if constexpr (S > 0) {
+        // the tile is TP / Wo whole output rows; a thread owns one strip of it (RB rows x 4 columns) and walks
+        // over the channels.  NQ is a multiple of the strip's row block, so a strip is wholly live or wholly not.
+        constexpr int IPC = TP / (4 * RB);       // strips per channel
+        constexpr int CSTEP = 256 / IPC;         // channels the workgroup covers per trip
+        const int item = tid % IPC;
+        const int W4 = G.Wo / 4;
+        const int cw = (item % W4) * 4, srow = (item / W4) * RB;      // first column / first tile row of the strip
+        const long long qa = q0 + (long long)srow * G.Wo + cw;        // first column (sample, pixel) of the strip
+        const bool live = qa < P.NQ;
+        const long long qs = live ? qa : 0;
+        const int n = (int)(qs / P.HW), r0 = (int)(qs % P.HW) / G.Wo;
+        const float* xb = x + (size_t)n * P.Cin * HWi + (size_t)(S * r0) * G.W + S * cw;
+        uint32_t rowmask = (1u << (S * (RB - 1) + 3)) - 1;
+        if (r0 == 0) rowmask &= ~1u;
+        if (S == 1 && r0 + RB == G.Ho) rowmask &= ~(1u << (RB + 1));
+        if (!live) rowmask = 0;
+        const bool left = cw > 0, right = cw + 4 < G.Wo;
+        const int colbase = srow * G.Wo + cw;    // column of the strip's first output inside the tile
+#pragma unroll 2
+        for (int c = tid / IPC; c < P.Cin; c += CSTEP) {
+            float k[9];
+#pragma unroll
+            for (int i = 0; i < 9; ++i) k[i] = kdw[c * 9 + i];
+            float out[RB][4];
+            dw_strip<S, RB>(xb + (size_t)c * HWi, G.W, k, rowmask, left, right, false, false, out);
+            float* zo = zl + ((size_t)(c >> 2) * TPP + colbase) * 4 + (c & 3);
+#pragma unroll
+            for (int rr = 0; rr < RB; ++rr)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) zo[(rr * G.Wo + i) * 4] = out[rr][i];
+        }
+    } else {
+        // any stride and map size: each of the thread's 4 columns has its own sample and pixel
+        constexpr int G4 = TP / 4;           // groups of 4 columns per tile
+        constexpr int CSTEP = 256 / G4;      // channels the workgroup covers per trip
         const int g4 = tid % G4;
         const long long qa = q0 + 4 * g4;
-        if constexpr (FAST) {
-            // the 4 columns qa..qa+3 are pixels p..p+3 of one row of one sample (HW % 4 == 0, so NQ % 4 == 0)
-            const bool live = qa < P.NQ;
-            const long long qs = live ? qa : 0;
-            const int n = (int)(qs / P.HW), p = (int)(qs % P.HW);
-            const int r = p / G.W, cw = p % G.W;
-            const float* xb = x + (size_t)n * P.Cin * HWi + p;
-            const bool rowok[3] = {live && r > 0, live, live && r + 1 < G.H};
-            const bool left = cw > 0, right = cw + 4 < G.W;
-            for (int c = tid / G4; c < P.Cin; c += CSTEP) {
-                const float* xc = xb + (size_t)c * HWi;
-                float k[9];
+        long long base[4];     // offset of the stencil's centre pixel in channel 0 of the column's sample
+        uint32_t taps[4];      // bit 3*i+j: tap (i, j) falls inside the map
 #pragma unroll
-                for (int i = 0; i < 9; ++i) k[i] = kdw[c * 9 + i];
-                float out[4] = {0.f, 0.f, 0.f, 0.f};
+        for (int i4 = 0; i4 < 4; ++i4) {
+            const long long q = qa + i4;
+            taps[i4] = 0;
+            base[i4] = 0;
+            if (q < P.NQ) {
+                const int n = (int)(q / P.HW), p = (int)(q % P.HW);
+                const int m = p / G.Wo, qq = p % G.Wo;
+                base[i4] = (long long)n * P.Cin * HWi + (long long)(G.s * m) * G.W + G.s * qq;
 #pragma unroll
-                for (int dr = 0; dr < 3; ++dr) {
-                    // rows outside the map are read at the centre row (always inside) and discarded
-                    const float* row = rowok[dr] ? xc + (dr - 1) * G.W : xc;
-                    const f32x4 mid = *(const f32x4*)row;
-                    const float lv = row[left ? -1 : 0], rv = row[right ? 4 : 3];
-                    float v[6];
-                    v[0] = (rowok[dr] && left) ? lv : 0.f;
-                    v[1] = rowok[dr] ? mid[0] : 0.f;
-                    v[2] = rowok[dr] ? mid[1] : 0.f;
-                    v[3] = rowok[dr] ? mid[2] : 0.f;
-                    v[4] = rowok[dr] ? mid[3] : 0.f;
-                    v[5] = (rowok[dr] && right) ? rv : 0.f;
+                for (int i = 0; i < 3; ++i)
 #pragma unroll
-                    for (int i = 0; i < 4; ++i)
-#pragma unroll
-                        for (int j = 0; j < 3; ++j) out[i] += k[dr * 3 + j] * v[i + j];
-                }
-                float* zo = zl + ((size_t)(c >> 2) * TP + 4 * g4) * 4 + (c & 3);
-#pragma unroll
-                for (int i = 0; i < 4; ++i) zo[4 * i] = out[i];
+                    for (int j = 0; j < 3; ++j) {
+                        const int rr = G.s * m + i - 1, cc = G.s * qq + j - 1;
+                        if (rr >= 0 && rr < G.H && cc >= 0 && cc < G.W) taps[i4] |= 1u << (3 * i + j);
+                    }
             }
-        } else {
-            // any stride and map size: each of the thread's 4 columns has its own sample and pixel
-            long long base[4];     // offset of the stencil's centre pixel in channel 0 of the column's sample
-            uint32_t taps[4];      // bit 3*i+j: tap (i, j) falls inside the map
+        }
+        for (int c = tid / G4; c < P.Cin; c += CSTEP) {
+            float k[9];
+#pragma unroll
+            for (int i = 0; i < 9; ++i) k[i] = kdw[c * 9 + i];
+            float* zo = zl + ((size_t)(c >> 2) * TPP + 4 * g4) * 4 + (c & 3);
 #pragma unroll
             for (int i4 = 0; i4 < 4; ++i4) {
-                const long long q = qa + i4;
-                taps[i4] = 0;
-                base[i4] = 0;
-                if (q < P.NQ) {
-                    const int n = (int)(q / P.HW), p = (int)(q % P.HW);
-                    const int m = p / G.Wo, qq = p % G.Wo;
-                    base[i4] = (long long)n * P.Cin * HWi + (long long)(G.s * m) * G.W + G.s * qq;
+                const float* xc = x + base[i4] + (long long)c * HWi;
+                float out = 0.f;
 #pragma unroll
-                    for (int i = 0; i < 3; ++i)
+                for (int i = 0; i < 3; ++i)
 #pragma unroll
-                        for (int j = 0; j < 3; ++j) {
-                            const int rr = G.s * m + i - 1, cc = G.s * qq + j - 1;
-                            if (rr >= 0 && rr < G.H && cc >= 0 && cc < G.W) taps[i4] |= 1u << (3 * i + j);
-                        }
-                }
-            }
-            for (int c = tid / G4; c < P.Cin; c += CSTEP) {
-                float k[9];
-#pragma unroll
-                for (int i = 0; i < 9; ++i) k[i] = kdw[c * 9 + i];
-                float* zo = zl + ((size_t)(c >> 2) * TP + 4 * g4) * 4 + (c & 3);
-#pragma unroll
-                for (int i4 = 0; i4 < 4; ++i4) {
-                    const float* xc = x + base[i4] + (long long)c * HWi;
-                    float out = 0.f;
-#pragma unroll
-                    for (int i = 0; i < 3; ++i)
-#pragma unroll
-                        for (int j = 0; j < 3; ++j)
-                            if (taps[i4] & (1u << (3 * i + j))) out += k[3 * i + j] * xc[(i - 1) * G.W + (j - 1)];
-                    zo[4 * i4] = out;
-                }
+                    for (int j = 0; j < 3; ++j)
+                        if (taps[i4] & (1u << (3 * i + j))) out += k[3 * i + j] * xc[(i - 1) * G.W + (j - 1)];
+                zo[4 * i4] = out;
             }
         }
     }
     __syncthreads();
 
     // ---------------- phase 2: the SCC tiles of this column tile, B operand from LDS
-    const int lane = tid & 63, wave = tid >> 6, col = lane & 31, kg = lane >> 5;
     const f32x4* zl4 = (const f32x4*)zl;
-    const Band& b = T.b;
-    const int f = lane & 31;  // this lane's A row (filter of the tile)
 
     // where this lane's columns go in y
     long long ycol[CP];
@@ -229,91 +359,62 @@ __global__ __launch_bounds__(256) void dw_scc_forward_lds(const float* __restric
         ycol[c] = (qs / P.HW) * (long long)P.Cout * P.HW + qs % P.HW;
     }
 
-    for (int ft = wave; ft < T.ntiles; ft += 4) {
-        const int ib = ft % T.IB, mb = ft / T.IB;
-        const int m = mb * T.TM + f / T.TI, i = ib * T.TI + f % T.TI;
-        long long kf = -1;
-        if (m < b.P) {
-            kf = (long long)(((long long)m * b.inv) % b.P) + (long long)b.P * i;
-            if (kf >= P.Cout) kf = -1;
-        }
-        const int sf = b.g * m;                 // window start of this lane's filter
-        const int c0 = b.g * mb * T.TM;         // window start of the tile's first filter column
-        const int cend = c0 + T.U;              // one past the tile's span (unwrapped channel axis)
-        const float* wrow = w + (kf >= 0 ? kf : 0) * P.L;
+    f32x16 acc[CP];
+#pragma unroll
+    for (int c = 0; c < CP; ++c)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[c][v] = 0.f;
 
-        f32x16 acc[CP];
-#pragma unroll
-        for (int c = 0; c < CP; ++c)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[c][v] = 0.f;
+    while (cur.ft < T.ntiles) {       // uniform over the wavefront
+        // this step's A operand, cut into bf16 pieces; then the next step's weights are requested
+        uint32_t ah[4], am[4], al[4];
+        split3<8>([&](int e) { return araw[e]; }, ah, am, al);
+        const Step nxt = next_of(cur);
+        load_a(nxt, araw);            // past the end: reads row 0 of w and is never used
 
-        for (int cb = c0 & ~15; cb < cend; cb += 64) {
-            // A operand of up to 4 chunks of 16 channels: this lane's 8 weights per chunk, cut into bf16 pieces
-            uint32_t ah[4][4], am[4][4], al[4][4];
+        {
+            int cw = cur.cb;
+            while (cw >= P.Cin) cw -= P.Cin;   // Cin and the chunk start are multiples of 16: a chunk never straddles the wrap
+            const int quad = (cw + 8 * kg) >> 2;
 #pragma unroll
-            for (int ch = 0; ch < 4; ++ch) {
-                const int j0 = cb + 16 * ch + 8 * kg - sf;   // weight index of the lane's first channel
-                float a[8];
-                if constexpr (AL4) {
-#pragma unroll
-                    for (int h = 0; h < 2; ++h) {
-                        const int j = j0 + 4 * h;
-                        const bool in = kf >= 0 && j >= 0 && j < P.L;
-                        const f32x4 v = *(const f32x4*)(wrow + (in ? j : 0));
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) a[4 * h + e] = in ? v[e] : 0.f;
-                    }
-                } else {
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) {
-                        const int j = j0 + e;
-                        const bool in = kf >= 0 && j >= 0 && j < P.L;
-                        const float v = wrow[in ? j : 0];
-                        a[e] = in ? v : 0.f;
-                    }
-                }
-                split3<8>([&](int e) { return a[e]; }, ah[ch], am[ch], al[ch]);
-            }
-#pragma unroll
-            for (int ch = 0; ch < 4; ++ch) {
-                const int cu = cb + 16 * ch;
-                if (cu >= cend) break;          // uniform over the wavefront
-                int cw = cu;
-                while (cw >= P.Cin) cw -= P.Cin;   // Cin and the chunk start are multiples of 16: a chunk never straddles the wrap
-                const int quad = (cw + 8 * kg) >> 2;
-#pragma unroll
-                for (int c = 0; c < CP; ++c) {
-                    const f32x4 b0 = zl4[(size_t)quad * TP + 32 * c + col];
-                    const f32x4 b1 = zl4[(size_t)(quad + 1) * TP + 32 * c + col];
-                    const float bv[8] = {b0[0], b0[1], b0[2], b0[3], b1[0], b1[1], b1[2], b1[3]};
-                    uint32_t bh[4], bm[4], bl[4];
-                    split3<8>([&](int e) { return bv[e]; }, bh, bm, bl);
-                    acc[c] = mfma_bf16<8>(al[ch], bh, acc[c]);
-                    acc[c] = mfma_bf16<8>(ah[ch], bl, acc[c]);
-                    acc[c] = mfma_bf16<8>(am[ch], bm, acc[c]);
-                    acc[c] = mfma_bf16<8>(am[ch], bh, acc[c]);
-                    acc[c] = mfma_bf16<8>(ah[ch], bm, acc[c]);
-                    acc[c] = mfma_bf16<8>(ah[ch], bh, acc[c]);
-                }
+            for (int c = 0; c < CP; ++c) {
+                const f32x4 b0 = zl4[(size_t)quad * TPP + 32 * c + col];
+                const f32x4 b1 = zl4[(size_t)(quad + 1) * TPP + 32 * c + col];
+                const float bv[8] = {b0[0], b0[1], b0[2], b0[3], b1[0], b1[1], b1[2], b1[3]};
+                uint32_t bh[4], bm[4], bl[4];
+                split3<8>([&](int e) { return bv[e]; }, bh, bm, bl);
+                acc[c] = mfma_bf16<8>(al, bh, acc[c]);
+                acc[c] = mfma_bf16<8>(ah, bl, acc[c]);
+                acc[c] = mfma_bf16<8>(am, bm, acc[c]);
+                acc[c] = mfma_bf16<8>(am, bh, acc[c]);
+                acc[c] = mfma_bf16<8>(ah, bm, acc[c]);
+                acc[c] = mfma_bf16<8>(ah, bh, acc[c]);
             }
         }
 
-        // accumulator register v of a lane holds tile row (v/4)*8 + kg*4 + v%4 at the lane's column
-        const int kmine = (int)kf;
+        if (nxt.ft != cur.ft) {
+            // the tile is complete: accumulator register v of a lane holds tile row (v/4)*8 + kg*4 + v%4 at the
+            // lane's column
+            const int kmine = (int)cur.kf;
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int row = (v >> 2) * 8 + kg * 4 + (v & 3);
-            const int kr = __shfl(kmine, row, 64);   // lane `row` computed that filter's index
-            if (kr < 0) continue;
+            for (int v = 0; v < 16; ++v) {
+                const int row = (v >> 2) * 8 + kg * 4 + (v & 3);
+                const int kr = __shfl(kmine, row, 64);   // lane `row` computed that filter's index
+                if (kr < 0) continue;
+#pragma unroll
+                for (int c = 0; c < CP; ++c)
+                    if (live[c]) __builtin_nontemporal_store(acc[c][v], y + ycol[c] + (long long)kr * P.HW);
+            }
 #pragma unroll
             for (int c = 0; c < CP; ++c)
-                if (live[c]) __builtin_nontemporal_store(acc[c][v], y + ycol[c] + (long long)kr * P.HW);
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[c][v] = 0.f;
         }
+        cur = nxt;
     }
 }
 
-DwTiling make_dw_tiling(const Problem& p, int TP)
+DwTiling make_dw_tiling(const Problem& p, int TP, const float* w)
 {
     DwTiling t;
     t.b = make_band(p);
@@ -325,35 +426,58 @@ DwTiling make_dw_tiling(const Problem& p, int TP)
     t.U = p.L + t.b.g * (t.TM - 1);
     t.nct = (p.NQ + TP - 1) / TP;
     t.chunk = (t.nct + 7) / 8;
+    t.al4 = t.b.g % 4 == 0 && p.L % 4 == 0 && ((uintptr_t)w & 15) == 0;
     return t;
 }
 
-// columns per workgroup: as many groups of 32 (4, 2 or 1) as leave every CU a workgroup and fit 64 KiB of LDS,
-// else the most that fit 128 KiB
-int pick_cp(const Problem& p)
+size_t fused_lds_bytes(const Problem& p, int cp) { return (size_t)4 * p.Cin * (32 * cp + 1); }
+
+// Rows per strip (4 or 2) when phase 1 can run on strips for tiles of 32*cp columns, else 0: stride 1 or 2, output
+// rows that are a multiple of 4 pixels and divide the tile, input maps of exactly stride times the output size,
+// and a strip height that divides both the rows of a tile and the rows of a map.
+int strip_rows(const DwGeom& g, int cp, const float* x)
 {
-    for (int cp = 4; cp >= 1; cp /= 2) {
-        const long long lds = (long long)p.Cin * 32 * cp * 4;
-        if (lds <= 64 * 1024 && (p.NQ + 32 * cp - 1) / (32 * cp) >= 256) return cp;
-    }
-    for (int cp = 4; cp >= 1; cp /= 2)
-        if ((long long)p.Cin * 32 * cp * 4 <= 64 * 1024) return cp;
-    return 1;
+    const int TP = 32 * cp;
+    if ((g.s != 1 && g.s != 2) || g.Wo % 4 != 0 || TP % g.Wo != 0 || g.H != g.s * g.Ho || g.W != g.s * g.Wo ||
+        ((uintptr_t)x & 15) != 0)
+        return 0;
+    const int rt = TP / g.Wo;
+    if (rt % 4 == 0 && g.Ho % 4 == 0) return 4;
+    if (rt % 2 == 0 && g.Ho % 2 == 0) return 2;
+    return 0;
 }
 
-template <int CP, bool AL4, bool FAST>
+// Columns per workgroup, in groups of 32 (2 or 1): two workgroups per CU where the LDS tile allows it (80 KiB each),
+// the wider tile when it still leaves every CU two workgroups, and a width on which phase 1 can run on strips
+// if there is one.
+int pick_cp(const Problem& p, const DwGeom& g, const float* x)
+{
+    int first = 0;
+    for (int cp = 2; cp >= 1; --cp) {
+        const bool fits = fused_lds_bytes(p, cp) <= 80 * 1024 || cp == 1;
+        const bool enough = (p.NQ + 32 * cp - 1) / (32 * cp) >= 512 || cp == 1;
+        if (!fits || !enough) continue;
+        if (!first) first = cp;
+        if (strip_rows(g, cp, x) > 0) return cp;
+    }
+    // no width of that choice runs on strips: a wider tile may (rows of 64 pixels need 64 columns)
+    if (fused_lds_bytes(p, 2) <= 80 * 1024 && strip_rows(g, 2, x) > 0) return 2;
+    return first;
+}
+
+template <int CP, int S, int RB>
 hipError_t launch_fused(const float* x, const float* kdw, const float* w, float* y, const Problem& p, const DwGeom& g,
                         hipStream_t st)
 {
-    const DwTiling t = make_dw_tiling(p, 32 * CP);
-    const size_t lds = (size_t)p.Cin * 32 * CP * sizeof(float);
+    const DwTiling t = make_dw_tiling(p, 32 * CP, w);
+    const size_t lds = fused_lds_bytes(p, CP);
     if (lds > 64 * 1024) {
         // more than 64 KiB of LDS per workgroup has to be allowed once per kernel (per process: one GPU is driven)
-        static const hipError_t allowed = hipFuncSetAttribute((const void*)dw_scc_forward_lds<CP, AL4, FAST>,
-                                                              hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024);
+        static const hipError_t allowed = hipFuncSetAttribute((const void*)dw_scc_forward_lds<CP, S, RB>,
+                                                              hipFuncAttributeMaxDynamicSharedMemorySize, 144 * 1024);
         if (allowed != hipSuccess) return allowed;
     }
-    dw_scc_forward_lds<CP, AL4, FAST><<<dim3((unsigned)(8 * t.chunk)), dim3(256), lds, st>>>(x, kdw, w, y, p, g, t);
+    dw_scc_forward_lds<CP, S, RB><<<dim3((unsigned)(8 * t.chunk)), dim3(256), lds, st>>>(x, kdw, w, y, p, g, t);
     return hipGetLastError();
 }
 
@@ -361,14 +485,30 @@ template <int CP>
 hipError_t launch_fused_cp(const float* x, const float* kdw, const float* w, float* y, const Problem& p, const DwGeom& g,
                            hipStream_t st)
 {
-    const Band b = make_band(p);
-    const bool al4 = b.g % 4 == 0 && p.L % 4 == 0 && ((uintptr_t)w & 15) == 0;
-    const bool fast = g.s == 1 && g.W % 4 == 0 && ((uintptr_t)x & 15) == 0;
-    if (al4)
-        return fast ? launch_fused<CP, true, true>(x, kdw, w, y, p, g, st)
-                    : launch_fused<CP, true, false>(x, kdw, w, y, p, g, st);
-    return fast ? launch_fused<CP, false, true>(x, kdw, w, y, p, g, st)
-                : launch_fused<CP, false, false>(x, kdw, w, y, p, g, st);
+    const int rb = strip_rows(g, CP, x);
+    if (rb == 0) return launch_fused<CP, 0, 1>(x, kdw, w, y, p, g, st);
+    if (g.s == 1)
+        return rb == 4 ? launch_fused<CP, 1, 4>(x, kdw, w, y, p, g, st) : launch_fused<CP, 1, 2>(x, kdw, w, y, p, g, st);
+    return rb == 4 ? launch_fused<CP, 2, 4>(x, kdw, w, y, p, g, st) : launch_fused<CP, 2, 2>(x, kdw, w, y, p, g, st);
+}
+
+template <typename T, int S>
+hipError_t launch_strips(const T* x, const T* kdw, T* z, int N, int C, const DwGeom& g, hipStream_t st)
+{
+    // taller strips read fewer halo rows per output; small problems take shorter ones to have enough threads
+    int rb = g.Ho % 4 == 0 ? 4 : g.Ho % 2 == 0 ? 2 : 1;
+    while (rb > 1 && (long long)N * C * (g.Ho / rb) * (g.Wo / 4) < 256 * 1024) rb /= 2;
+    const long long items = (long long)N * C * (g.Ho / rb) * (g.Wo / 4);
+    long long blocks = (items + 255) / 256;
+    if (blocks > (1ll << 20)) blocks = 1ll << 20;   // the kernel strides over what is left
+    const dim3 grid((unsigned)blocks), block(256);
+    if (rb == 4)
+        depthwise3x3_strips<T, S, 4><<<grid, block, 0, st>>>(x, kdw, z, C, g, items);
+    else if (rb == 2)
+        depthwise3x3_strips<T, S, 2><<<grid, block, 0, st>>>(x, kdw, z, C, g, items);
+    else
+        depthwise3x3_strips<T, S, 1><<<grid, block, 0, st>>>(x, kdw, z, C, g, items);
+    return hipGetLastError();
 }
 
 }  // namespace
@@ -376,15 +516,14 @@ hipError_t launch_fused_cp(const float* x, const float* kdw, const float* w, flo
 template <typename T>
 hipError_t launch_depthwise3x3(const T* x, const T* kdw, T* z, int N, int C, const DwGeom& g, hipStream_t st)
 {
-    const long long outs = (long long)N * C * g.Ho * g.Wo;
-    const bool vec = g.s == 1 && g.W % 4 == 0;
-    const long long items = vec ? outs / 4 : outs;
+    const bool strips = (g.s == 1 || g.s == 2) && g.Wo % 4 == 0 && g.H == g.s * g.Ho && g.W == g.s * g.Wo &&
+                        (((uintptr_t)x | (uintptr_t)z) & (4 * sizeof(T) - 1)) == 0 &&
+                        (long long)N * C * g.Ho * (g.Wo / 4) < (1ll << 31);
+    if (strips) return g.s == 1 ? launch_strips<T, 1>(x, kdw, z, N, C, g, st) : launch_strips<T, 2>(x, kdw, z, N, C, g, st);
+    const long long items = (long long)N * C * g.Ho * g.Wo;
     long long blocks = (items + 255) / 256;
-    if (blocks > (1ll << 20)) blocks = 1ll << 20;   // the kernel strides over what is left
-    if (vec)
-        depthwise3x3_kernel<T, true><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(x, kdw, z, C, g, items);
-    else
-        depthwise3x3_kernel<T, false><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(x, kdw, z, C, g, items);
+    if (blocks > (1ll << 20)) blocks = 1ll << 20;
+    depthwise3x3_kernel<T><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(x, kdw, z, C, g, items);
     return hipGetLastError();
 }
 
@@ -393,19 +532,21 @@ template hipError_t launch_depthwise3x3<bf16_t>(const bf16_t*, const bf16_t*, bf
                                                 hipStream_t);
 
 // The fused kernel takes layers whose channel count is a multiple of 16 (a 16-channel chunk of the matrix
-// instruction then never straddles the cyclic wrap) and whose z tile of 32 columns fits 128 KiB of LDS.
+// instruction then never straddles the cyclic wrap) and whose z tile of 32 columns fits 144 KiB of LDS.
 bool dw_forward_fused_eligible(const Problem& p)
 {
-    return p.Cin % 16 == 0 && (long long)p.Cin * 32 * 4 <= 128 * 1024 && p.L >= 8 && p.Cin < 65536 &&
-           (long long)p.NQ * p.Cout * 4 < (1ll << 40);
+    return p.Cin % 16 == 0 && fused_lds_bytes(p, 1) <= 144 * 1024 && p.Cin < 65536;
 }
+
+// Where it also pays: a workgroup computes every filter tile of its columns, so the grid has one workgroup per 32
+// or 64 columns; measured against the two stages run one after the other it wins from 16384 columns up (two
+// workgroups per CU) and loses below (the deep layers of the MobileNet-shaped stack: 512 to 8192 columns).
+bool dw_forward_fused_preferred(const Problem& p) { return dw_forward_fused_eligible(p) && p.NQ >= 16384; }
 
 hipError_t launch_dw_forward_fused(const float* x, const float* kdw, const float* w, float* y, const Problem& p,
                                    const DwGeom& g, hipStream_t st)
 {
-    const int cp = pick_cp(p);
-    if (cp == 4) return launch_fused_cp<4>(x, kdw, w, y, p, g, st);
-    if (cp == 2) return launch_fused_cp<2>(x, kdw, w, y, p, g, st);
+    if (pick_cp(p, g, x) == 2) return launch_fused_cp<2>(x, kdw, w, y, p, g, st);
     return launch_fused_cp<1>(x, kdw, w, y, p, g, st);
 }
 

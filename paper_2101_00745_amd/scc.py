@@ -17,7 +17,7 @@ SCC_F32, SCC_BF16 = 0, 1
 SYMBOLS = ("scc_window_params", "scc_forward", "scc_backward_input",
            "scc_backward_weight_workspace_bytes", "scc_backward_weight", "scc_backward_weight_static",
            "scc_backward_workspace_bytes", "scc_backward",
-           "scc_depthwise3x3_out", "scc_depthwise3x3_forward", "scc_dw_forward_workspace_bytes", "scc_dw_forward",
+           "scc_depthwise3x3_out", "scc_depthwise3x3_forward", "scc_dw_forward_workspace_bytes", "scc_dw_forward_fusable", "scc_dw_forward",
            "scc_status_string")
 STATIC_SCRATCH_BYTES = 8 << 20    # SCC_STATIC_SCRATCH_BYTES of include/scc.h
 
@@ -65,6 +65,8 @@ def load():
     dw_shape = [c_int] * 7 + [c_dbl, c_int]     # N, Cin, Cout, H, W, dw_stride, cg, co, dtype
     lib.scc_dw_forward_workspace_bytes.argtypes = dw_shape
     lib.scc_dw_forward_workspace_bytes.restype = c_sz
+    lib.scc_dw_forward_fusable.argtypes = dw_shape
+    lib.scc_dw_forward_fusable.restype = c_int
     lib.scc_dw_forward.argtypes = [c_vp] * 4 + dw_shape + [c_vp, c_sz, c_vp]
     lib.scc_dw_forward.restype = c_int
     lib.scc_status_string.argtypes = [c_int]
@@ -256,9 +258,19 @@ def scc_dw_forward_workspace_bytes(N, Cin, Cout, H, W, dw_stride, cg, co, dtype=
     return int(load().scc_dw_forward_workspace_bytes(N, Cin, Cout, H, W, int(dw_stride), cg, float(co), code))
 
 
-def scc_dw_forward(x, kdw, w, cg, co, dw_stride=1, out=None, workspace=None):
+def scc_dw_forward_fusable(N, Cin, Cout, H, W, dw_stride, cg, co, dtype=torch.float32):
+    """True when the fused kernel can run the layer (it then also runs without a workspace)."""
+    code = SCC_F32 if dtype == torch.float32 else SCC_BF16
+    r = int(load().scc_dw_forward_fusable(N, Cin, Cout, H, W, int(dw_stride), cg, float(co), code))
+    _check(min(r, 0))
+    return r == 1
+
+
+def scc_dw_forward(x, kdw, w, cg, co, dw_stride=1, out=None, workspace=None, fused=None):
     """y = SCC(DW3x3(x; kdw); w), the forward of a DW + SCC block: x [N,Cin,H,W], kdw [Cin,3,3], w [Cout,Cin//cg]
-    -> y [N,Cout,Ho,Wo]."""
+    -> y [N,Cout,Ho,Wo].  fused=None: the path the library prefers (a workspace is allocated when it asks for
+    one); fused=True: no workspace is passed, so the fused kernel runs or the call is refused; fused=False: the
+    two stages through a workspace, also where the library would fuse."""
     dev = _dev(x, kdw, w)
     N, Cin, H, W = x.shape
     Cout = w.shape[0]
@@ -267,9 +279,14 @@ def scc_dw_forward(x, kdw, w, cg, co, dw_stride=1, out=None, workspace=None):
     if w.dtype != x.dtype or w.dim() != 2 or (cg >= 1 and Cin % cg == 0 and w.shape[1] != Cin // cg):
         raise ValueError("w must be [Cout, Cin//cg] with the dtype of x")
     Ho, Wo = scc_depthwise3x3_out(H, dw_stride), scc_depthwise3x3_out(W, dw_stride)
+    if fused is False:
+        z = scc_depthwise3x3_forward(x, kdw, dw_stride)
+        return scc_forward(z, w, cg, co, out=out)
     code = _dtype_code(x)
     need = int(load().scc_dw_forward_workspace_bytes(N, Cin, Cout, H, W, int(dw_stride), cg, float(co), code))
-    if workspace is None and need > 0:
+    if fused:
+        workspace = None
+    elif workspace is None and need > 0:
         workspace = torch.empty(need, dtype=torch.uint8, device=dev)
     y = torch.empty((N, Cout, Ho, Wo), dtype=x.dtype, device=dev) if out is None else out
     if out is not None:

@@ -151,6 +151,13 @@ def test_dw_block_null_pointers_and_workspace():
     # layers the fused kernel takes need no workspace
     assert lib.scc_dw_forward_workspace_bytes(128, 256, 256, 16, 16, 1, 4, 0.5, 0) == 0
     assert lib.scc_dw_forward_workspace_bytes(128, 256, 256, 16, 16, 1, 4, 0.5, 1) == 128 * 256 * 256 * 2   # bf16
+    # a layer the fused kernel can run but that is faster in two stages: a workspace is asked for, and the query says
+    # that a call without one is served by the fused kernel
+    deep = (128, 512, 512, 4, 4, 1, 2, 0.5, 0)
+    assert lib.scc_dw_forward_workspace_bytes(*deep) == 128 * 512 * 16 * 4 and lib.scc_dw_forward_fusable(*deep) == 1
+    assert lib.scc_dw_forward_fusable(*shape) == 0 and lib.scc_dw_forward_fusable(128, 256, 256, 16, 16, 1, 4, 0.5, 1) == 0
+    assert lib.scc_dw_forward_fusable(128, 256, 256, 16, 16, 0, 4, 0.5, 0) == -2
+    assert lib.scc_dw_forward_fusable(128, 256, 256, 16, 16, 1, 4, 0.5, 7) == -4
     assert lib.scc_depthwise3x3_out(32, 2) == 16 and lib.scc_depthwise3x3_out(7, 2) == 4
     assert lib.scc_depthwise3x3_out(0, 1) == -2 and lib.scc_depthwise3x3_out(5, 0) == -2
 

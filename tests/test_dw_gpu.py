@@ -49,20 +49,27 @@ def layer_of(N, Cin, Cout, H, W, cg, co, idx=0):
                     co=co, layer=idx)
 
 
-def check_block(S, layer, dw_stride, dtype=torch.float32, expect_fused=None):
+def check_block(S, layer, dw_stride, dtype=torch.float32, expect_fusable=None, paths=("auto",)):
+    """Runs the block's forward along each of `paths` ("auto": the library's choice, "fused": no workspace, so the
+    fused kernel must run, "two": the two stages) and holds every result to the oracle."""
     xin, kdw, w = Wk.make_block_inputs(layer, dw_stride)
     xd, kd, wd = to_dev(xin, dtype), to_dev(kdw, dtype), to_dev(w, dtype)
-    need = S.scc_dw_forward_workspace_bytes(layer.N, layer.Cin, layer.Cout, xin.shape[2], xin.shape[3], dw_stride,
-                                            layer.cg, layer.co, dtype)
-    if expect_fused is not None:
-        assert (need == 0) == expect_fused, "%s: workspace %d, expected fused=%s" % (layer.name, need, expect_fused)
-    y = S.scc_dw_forward(xd, kd, wd, layer.cg, layer.co, dw_stride)
-    torch.cuda.synchronize()
+    shape = (layer.N, layer.Cin, layer.Cout, xin.shape[2], xin.shape[3], dw_stride, layer.cg, layer.co, dtype)
+    fusable = S.scc_dw_forward_fusable(*shape)
+    if expect_fusable is not None:
+        assert fusable == expect_fusable, "%s: fusable=%s" % (layer.name, fusable)
+    if not fusable:
+        assert S.scc_dw_forward_workspace_bytes(*shape) > 0
     ref = O.depthwise_scc_forward(host(xd), host(kd), host(wd), layer.cg, layer.co, dw_stride)
-    assert tuple(y.shape) == ref.shape and y.dtype == dtype
-    e = rel_err(host(y), ref)
-    assert e <= TOL[dtype], "%s stride %d %s: rel err %.3e > %.1e" % (layer.name, dw_stride, dtype, e, TOL[dtype])
-    return e
+    worst = 0.0
+    for path in paths:
+        y = S.scc_dw_forward(xd, kd, wd, layer.cg, layer.co, dw_stride, fused={"auto": None, "fused": True, "two": False}[path])
+        torch.cuda.synchronize()
+        assert tuple(y.shape) == ref.shape and y.dtype == dtype
+        e = rel_err(host(y), ref)
+        assert e <= TOL[dtype], "%s stride %d %s %s: rel err %.3e > %.1e" % (layer.name, dw_stride, dtype, path, e, TOL[dtype])
+        worst = max(worst, e)
+    return worst
 
 
 # ------------------------------------------------------------------------------------- the depthwise stage alone
@@ -112,7 +119,8 @@ FUSED_SMALL = [
 @pytest.mark.parametrize("cfg", FUSED_SMALL)
 def test_fused_block_small(S, cfg):
     N, Cin, Cout, H, W, cg, co, s = cfg
-    check_block(S, layer_of(N, Cin, Cout, H, W, cg, co, idx=FUSED_SMALL.index(cfg) % 10), s, expect_fused=True)
+    check_block(S, layer_of(N, Cin, Cout, H, W, cg, co, idx=FUSED_SMALL.index(cfg) % 10), s, expect_fusable=True,
+                paths=("fused", "auto", "two"))
 
 
 @pytest.mark.parametrize("cfg", [(2, 512, 512, 4, 4, 2, 0.5, 1), (3, 1024, 1024, 2, 2, 2, 0.5, 1),
@@ -120,7 +128,7 @@ def test_fused_block_small(S, cfg):
 def test_fused_block_many_channels(S, cfg):
     """Channel counts whose LDS tile is 64 to 128 KiB (the largest the kernel takes)."""
     N, Cin, Cout, H, W, cg, co, s = cfg
-    check_block(S, layer_of(N, Cin, Cout, H, W, cg, co), s, expect_fused=True)
+    check_block(S, layer_of(N, Cin, Cout, H, W, cg, co), s, expect_fusable=True, paths=("fused", "auto"))
 
 
 # ------------------------------------------------------------------------------------- layers the fused kernel declines
@@ -130,13 +138,13 @@ UNFUSED = [(2, 24, 16, 6, 6, 2, 0.5, 1), (3, 40, 40, 5, 7, 4, 0.5, 2), (1, 2048,
 @pytest.mark.parametrize("cfg", UNFUSED)
 def test_two_stage_path_fp32(S, cfg):
     N, Cin, Cout, H, W, cg, co, s = cfg
-    check_block(S, layer_of(N, Cin, Cout, H, W, cg, co), s, expect_fused=False)
+    check_block(S, layer_of(N, Cin, Cout, H, W, cg, co), s, expect_fusable=False)
 
 
 @pytest.mark.parametrize("cfg", [FUSED_SMALL[0], FUSED_SMALL[2], FUSED_SMALL[4], UNFUSED[0]])
 def test_two_stage_path_bf16(S, cfg):
     N, Cin, Cout, H, W, cg, co, s = cfg
-    check_block(S, layer_of(N, Cin, Cout, H, W, cg, co), s, dtype=torch.bfloat16, expect_fused=False)
+    check_block(S, layer_of(N, Cin, Cout, H, W, cg, co), s, dtype=torch.bfloat16, expect_fusable=False)
 
 
 # ------------------------------------------------------------------------------------- the paper-shaped layers
@@ -145,26 +153,39 @@ def test_stack_layers_every_element(S, i):
     """Every layer of the MobileNet-shaped stack with its depthwise stage in front (stride 2 where the map halves),
     at a batch of 8 so that the oracle finishes in seconds; the full batch is sampled below."""
     layer = dataclasses.replace(Wk.STACK[i], N=8)
-    check_block(S, layer, Wk.STACK_DW_STRIDE[i], expect_fused=True)
+    check_block(S, layer, Wk.STACK_DW_STRIDE[i], expect_fusable=True, paths=("fused", "auto"))
 
 
 def test_metric_layer_block_every_element(S):
-    check_block(S, dataclasses.replace(Wk.METRIC, N=16), 1, expect_fused=True)
+    check_block(S, dataclasses.replace(Wk.METRIC, N=16), 1, expect_fusable=True, paths=("fused", "auto"))
 
 
-@pytest.mark.parametrize("which", ["metric", "stack0", "stack5", "stack12"])
-def test_full_batch_sampled_samples(S, which):
+@pytest.mark.parametrize("path", ["auto", "fused"])
+@pytest.mark.parametrize("which", ["metric", "stack0", "stack1", "stack5", "stack12"])
+def test_full_batch_sampled_samples(S, which, path):
     """The full-size launch (the one the benchmark times), checked on the first, a middle and the last sample: the
-    oracle runs on those samples alone, which is exact because samples never mix."""
-    layer, s = {"metric": (Wk.METRIC, 1), "stack0": (Wk.STACK[0], 1), "stack5": (Wk.STACK[5], 2),
+    oracle runs on those samples alone, which is exact because samples never mix.  "auto" is the path the library
+    picks for the layer (fused for the first three, two stages for the deep ones), "fused" forces the fused kernel."""
+    layer, s = {"metric": (Wk.METRIC, 1), "stack0": (Wk.STACK[0], 1), "stack1": (Wk.STACK[1], 2), "stack5": (Wk.STACK[5], 2),
                 "stack12": (Wk.STACK[12], 1)}[which]
     xin, kdw, w = Wk.make_block_inputs(layer, s)
     y = S.scc_dw_forward(to_dev(xin, torch.float32), to_dev(kdw, torch.float32), to_dev(w, torch.float32), layer.cg,
-                         layer.co, s)
+                         layer.co, s, fused=None if path == "auto" else True)
     torch.cuda.synchronize()
     pick = [0, layer.N // 2 + 1, layer.N - 1]
     ref = O.depthwise_scc_forward(xin[pick], kdw, w, layer.cg, layer.co, s)
     assert rel_err(host(y[pick]), ref) <= TOL[torch.float32]
+
+
+def test_library_prefers_fusing_only_where_it_pays(S):
+    """Layers with at least 16384 output pixels over the batch are fused by the library's own choice (no workspace
+    asked for); smaller fusable layers ask for one, and run fused only when none is passed."""
+    big = (128, 256, 256, 16, 16, 1, 4, 0.5)
+    small = (128, 512, 512, 4, 4, 1, 2, 0.5)
+    assert S.scc_dw_forward_fusable(*big) and S.scc_dw_forward_workspace_bytes(*big) == 0
+    assert S.scc_dw_forward_fusable(*small) and S.scc_dw_forward_workspace_bytes(*small) == 128 * 512 * 16 * 4
+    assert not S.scc_dw_forward_fusable(*big, dtype=torch.bfloat16)
+    assert not S.scc_dw_forward_fusable(2, 24, 16, 6, 6, 1, 2, 0.5)
 
 
 def test_fused_equals_two_stages_closely(S):
@@ -173,8 +194,8 @@ def test_fused_equals_two_stages_closely(S):
     layer = dataclasses.replace(Wk.METRIC, N=4)
     xin, kdw, w = Wk.make_block_inputs(layer, 1)
     xd, kd, wd = (to_dev(a, torch.float32) for a in (xin, kdw, w))
-    fused = S.scc_dw_forward(xd, kd, wd, layer.cg, layer.co, 1)
-    two = S.scc_forward(S.scc_depthwise3x3_forward(xd, kd, 1), wd, layer.cg, layer.co)
+    fused = S.scc_dw_forward(xd, kd, wd, layer.cg, layer.co, 1, fused=True)
+    two = S.scc_dw_forward(xd, kd, wd, layer.cg, layer.co, 1, fused=False)
     torch.cuda.synchronize()
     assert rel_err(host(fused), host(two).astype(np.float64)) <= 2e-6
 
@@ -183,8 +204,8 @@ def test_repeatable_bitwise(S):
     layer = layer_of(5, 64, 48, 12, 12, 4, 0.5)
     xin, kdw, w = Wk.make_block_inputs(layer, 2)
     xd, kd, wd = (to_dev(a, torch.float32) for a in (xin, kdw, w))
-    a = S.scc_dw_forward(xd, kd, wd, layer.cg, layer.co, 2)
-    b = S.scc_dw_forward(xd, kd, wd, layer.cg, layer.co, 2)
+    a = S.scc_dw_forward(xd, kd, wd, layer.cg, layer.co, 2, fused=True)
+    b = S.scc_dw_forward(xd, kd, wd, layer.cg, layer.co, 2, fused=True)
     torch.cuda.synchronize()
     assert torch.equal(a, b)
 
@@ -197,7 +218,7 @@ def test_output_buffer_is_fully_overwritten(S):
     n = layer.N * layer.Cout * layer.HW
     buf = torch.full((n + 64,), float("nan"), device="cuda")
     out = buf[:n].view(layer.N, layer.Cout, layer.H, layer.W)
-    S.scc_dw_forward(xd, kd, wd, layer.cg, layer.co, 1, out=out)
+    S.scc_dw_forward(xd, kd, wd, layer.cg, layer.co, 1, out=out, fused=True)
     torch.cuda.synchronize()
     assert not torch.isnan(out).any() and torch.isnan(buf[n:]).all()
     assert rel_err(host(out), O.depthwise_scc_forward(xin, kdw, w, layer.cg, layer.co, 1)) <= 2e-5
