@@ -204,6 +204,17 @@ int scc_backward(const void* x, const void* dy, const void* w, void* dx, void* d
     if (dtype == SCC_F32 && aligned && scc::backward_fused_eligible(p))
         return launch_status(scc::launch_backward_fused((const float*)x, (const float*)dy, (const float*)w, (float*)dx,
                                                         (float*)dw, (float*)workspace, p, (hipStream_t)stream));
+    // layers both matrix-core kernels take: their two grids as one launch
+    if (dtype == SCC_F32) {
+        if (scc::backward_merged_applicable((const float*)x, (const float*)dy, (const float*)dx, p))
+            return launch_status(scc::launch_backward_merged((const float*)x, (const float*)dy, (const float*)w,
+                                                             (float*)dx, (float*)dw, (float*)workspace, p,
+                                                             (hipStream_t)stream));
+    } else if (scc::backward_merged_applicable((const scc::bf16_t*)x, (const scc::bf16_t*)dy, (const scc::bf16_t*)dx, p)) {
+        return launch_status(scc::launch_backward_merged((const scc::bf16_t*)x, (const scc::bf16_t*)dy,
+                                                         (const scc::bf16_t*)w, (scc::bf16_t*)dx, (float*)dw,
+                                                         (float*)workspace, p, (hipStream_t)stream));
+    }
     // every other layer: the two passes one after the other
     const int r1 = scc_backward_input(dy, w, dx, N, Cin, Cout, H, W, cg, co, dtype, stream);
     if (r1 != SCC_OK) return r1;

@@ -116,6 +116,13 @@ size_t backward_fused_workspace(const Problem& p);  // bytes of K-split partials
 hipError_t launch_backward_fused(const float* x, const float* dy, const float* w, float* dx, float* dw,
                                  float* workspace, const Problem& p, hipStream_t st);
 
+// Both gradients in one launch, the two matrix-core kernels side by side in one grid (scc_bwd_merged.hip);
+// needs the workspace of the grad-weight pass
+template <typename T> bool backward_merged_applicable(const T* x, const T* dy, const T* dx, const Problem& p);
+template <typename T>
+hipError_t launch_backward_merged(const T* x, const T* dy, const T* w, T* dx, float* dw, float* workspace,
+                                  const Problem& p, hipStream_t st);
+
 // Depthwise 3x3 stage and the fused DW + SCC forward (scc_dw_fwd.hip); `p` describes the SCC on the Ho x Wo map
 template <typename T>
 hipError_t launch_depthwise3x3(const T* x, const T* kdw, T* z, int N, int C, const DwGeom& g, hipStream_t st);
