@@ -29,8 +29,8 @@ F32_MATRIX_PEAK = 157.3e12     # dense fp32 matrix peak, flop/s
 BF16_MATRIX_PEAK = 2.5e15      # dense bf16 matrix peak, flop/s
 # HBM bytes per launch on the metric layer, from two rocprofv3 --pmc runs of the build named below (FETCH_SIZE
 # scaled by the factor a plain device copy gives, WRITE_SIZE by 1.0): profiles/scc_metric_layer_kernels.md
-TRAFFIC_PROFILED_BUILD = "commit 22354b9 (kernels unchanged since); profiles/scc_metric_layer_kernels.md"
-MEASURED_TRAFFIC_BYTES = {"metric": {'fwd': 67918065, 'bwi': 67898318, 'bww': 71458725, 'bwd': 105613053}}
+TRAFFIC_PROFILED_BUILD = "commit 24f3e35; profiles/scc_metric_layer_kernels.md"
+MEASURED_TRAFFIC_BYTES = {"metric": {"fwd": 67917035, "bwi": 67876755, "bww": 69266774 + 2190052, "bwd": 103423195 + 2190052}}
 KERNELS = {"fwd": ["forward_mfma32"], "bwi": ["backward_input_mfma32"],
            "bww": ["backward_weight_mfma32", "backward_weight_reduce"],
            "bwd": ["backward_fused_lds32", "backward_weight_reduce"]}
@@ -62,6 +62,9 @@ def parse():
                     help="run every configuration's entry points once each, a 16-byte membw_read launch before each "
                          "as a separator, and print the order: under `rocprofv3 --kernel-trace` the trace then shows "
                          "which kernels every configuration dispatched")
+    ap.add_argument("--block-trace", action="store_true",
+                    help="run the forward of the DW + SCC block on the metric layer (fused kernel, then the two stages) "
+                         "on rotating buffers and exit: the run a profiler wraps for the block's kernels")
     return ap.parse_args()
 
 
@@ -291,13 +294,13 @@ def sweep(S, Wk, torch, steps, warmup, path):
           file=sys.stderr, flush=True)
 
 
-def block_sweep(S, Wk, torch, replays_floor=MIN_REPLAYS):
+def block_sweep(S, Wk, torch, replays_floor=MIN_REPLAYS, layers=None):
     """Forward of the DW + SCC block (depthwise 3x3 stage in front of the SCC; stride 2 where the stack's map halves)
     on the metric layer and the 13 stack layers, fp32: the call as the library dispatches it (`auto`), the fused
     kernel forced, and the two stages run one after the other, each on cold rotating buffers."""
     dev = torch.device("cuda:0")
     out = []
-    for layer, s in [(Wk.METRIC, 1)] + list(zip(Wk.STACK, Wk.STACK_DW_STRIDE)):
+    for layer, s in (layers or [(Wk.METRIC, 1)] + list(zip(Wk.STACK, Wk.STACK_DW_STRIDE))):
         xin, kdw, w = Wk.make_block_inputs(layer, s)
         out_bytes = 4 * layer.N * layer.Cout * layer.HW
         R = max(2, min(256, -(-ROTATE_BYTES // max(xin.nbytes, out_bytes))))
@@ -330,8 +333,10 @@ def block_sweep(S, Wk, torch, replays_floor=MIN_REPLAYS):
               (layer.name, s, alg / 1e6, us["auto"], "fused" if out[-1]["library_fuses"] else "two stages", us["fused"],
                us["two_stages"], out[-1]["bound_us"]), file=sys.stderr, flush=True)
         del sets, ws, z
-    print("DW + SCC forward over the 13 stack layers: %.1f us as dispatched, %.1f us in two stages everywhere" %
-          (sum(r["us"]["auto"] for r in out[1:]), sum(r["us"]["two_stages"] for r in out[1:])), file=sys.stderr, flush=True)
+    if layers is None:
+        print("DW + SCC forward over the 13 stack layers: %.1f us as dispatched, %.1f us in two stages everywhere" %
+              (sum(r["us"]["auto"] for r in out[1:]), sum(r["us"]["two_stages"] for r in out[1:])), file=sys.stderr,
+              flush=True)
     return out
 
 
@@ -361,6 +366,14 @@ def dispatch_trace(S, Wk, torch, copy_lib):
             torch.cuda.synchronize()
             order.append("%s %s %s" % (layer.name, "f32" if dtype == torch.float32 else "bf16", name))
         del xd, wd, dyd
+    for layer, s in [(Wk.METRIC, 1)] + list(zip(Wk.STACK, Wk.STACK_DW_STRIDE)):
+        xin, kdw, w = Wk.make_block_inputs(layer, s)
+        xd, kd, wd = (torch.from_numpy(a).to(dev) for a in (xin, kdw, w))
+        copy_lib.membw_read_bytes(sink.data_ptr(), sink.data_ptr() + 64, 16, None)
+        S.scc_dw_forward(xd, kd, wd, layer.cg, layer.co, s)
+        torch.cuda.synchronize()
+        order.append("%s f32 scc_dw_forward(stride=%d)" % (layer.name, s))
+        del xd, kd, wd
     print("\n".join(order), flush=True)
 
 
@@ -381,6 +394,9 @@ def main():
     copy_lib = load_membw()
     if args.dispatch_trace:
         dispatch_trace(S, Wk, torch, copy_lib)
+        return
+    if args.block_trace:
+        print(json.dumps(block_sweep(S, Wk, torch, layers=[(Wk.METRIC, 1)])[0]))
         return
     if args.sweep:
         sweep(S, Wk, torch, min(args.steps, 64), min(args.warmup, 8), args.sweep)

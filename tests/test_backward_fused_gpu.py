@@ -102,6 +102,20 @@ def test_backward_matches_the_separate_passes_and_repeats_bitwise(S):
         assert float((dw1 - dws).abs().max()) <= 2e-5 * scale_w
 
 
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])
+@pytest.mark.parametrize("layer", OTHER[:5] + [Wk.STACK[6], Wk.STACK[11], Wk.METRIC_SWEEP[1]], ids=lambda l: l.name)
+def test_one_launch_for_both_passes_is_bitwise_the_separate_passes(S, layer, dtype):
+    """Layers the fused kernel declines run the grad-weight and grad-input kernels as two ranges of one grid: same
+    tiles, same arithmetic, same summation order, so dx and dw equal those of the separate entry points bit for bit."""
+    x, w, dy = Wk.make_inputs(layer)
+    xd, wd, dyd = (torch.from_numpy(a).to(dtype).cuda() for a in (x, w, dy))
+    dx1, dw1 = S.scc_backward(xd, dyd, wd, layer.cg, layer.co)
+    dxs = S.scc_backward_input(dyd, wd, layer.Cin, layer.cg, layer.co)
+    dws = S.scc_backward_weight(xd, dyd, layer.cg, layer.co)
+    torch.cuda.synchronize()
+    assert torch.equal(dx1, dxs) and torch.equal(dw1, dws)
+
+
 def test_backward_outputs_overwritten_and_workspace_contents_do_not_matter(S):
     layer = small("f_256_16x16", 4, 256, 256, 16, 16, 4, 0.5)
     x, w, dy = Wk.make_inputs(layer)
