@@ -328,6 +328,11 @@ inline BwwTiling make_tiling(const Problem& p)
             t.NPT = npt;
         }
     }
+    // layers with few columns are bound by latencies, not by operand rows: the narrow tile gives them more
+    // workgroups per K-split (so fewer splits to reduce) and a third less LDS per workgroup, which lets more of
+    // them, and of the grad-input workgroups that share their grid in scc_backward, be resident (measured on
+    // the 2x2 to 8x8 layers of the stack: 1-3 us per pass, except for spans of 512 channels)
+    if (p.NQ <= 8192 && t.U <= 256) t.NPT = 1;
     t.NSC = (t.U + 32 * t.NPT - 1) / (32 * t.NPT);
     t.NQ4 = (int)((p.NQ + 3) / 4);   // the last group is partial when N*H*W is not a multiple of 4
     // about one workgroup per CU (one wavefront per SIMD, deep prefetch), at least 32 column groups per wavefront
