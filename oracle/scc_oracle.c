@@ -30,6 +30,12 @@
  *                       the input, the tap (i, j) reading the pixel
  *                       (m + i - 1, n + j - 1); it is the stage whose output the
  *                       SCC consumes in a DW + SCC block (Section 3.1).
+ *   depthwise grads   - the derivatives of Eq. 2 with respect to its input and
+ *                       its filters (the paper trains DW + SCC blocks end to end,
+ *                       Section 5, and gives no formula): every product
+ *                       kdw[a,i,j] * x[n,a,r,c] of the forward sum that forms
+ *                       z[n,a,m,q] sends dz[n,a,m,q] * kdw[a,i,j] to dx[n,a,r,c]
+ *                       and dz[n,a,m,q] * x[n,a,r,c] to dkdw[a,i,j].
  *
  * Readings taken where the paper is silent:
  *   - overlap in channels is int(co * group_width) with C truncation of the
@@ -53,7 +59,10 @@
  * cases, the channel-stack composition, dense brute force, invariants and
  * finite differences; the depthwise stage against a library grouped
  * convolution, one-tap filters (pure shifts), tap counts at the border and a
- * dense matrix built tap by tap.  Nothing in this file is "parity unpinned".
+ * dense matrix built tap by tap; its two gradients against a library's
+ * automatic differentiation of the grouped convolution, the transpose of that
+ * dense matrix, the adjoint identity and central finite differences.  Nothing
+ * in this file is "parity unpinned".
  */
 #include <stddef.h>
 #include <stdlib.h>
@@ -219,6 +228,42 @@ int scc_oracle_depthwise3x3(const double *x, const double *kdw, double *z,
                 }
             }
         }
+    }
+    return 0;
+}
+
+/* dx[n,a,r,c] and dkdw[a,i,j]: the forward sum of Eq. 2 walked once more, every
+ * product handing its share of dz to both of its factors' gradients.
+ * dx: N*C*H*W, dkdw: C*9; both are overwritten. */
+int scc_oracle_depthwise3x3_backward(const double *x, const double *kdw, const double *dz,
+                                     double *dx, double *dkdw,
+                                     int N, int C, int H, int W, int stride)
+{
+    if (N <= 0 || C <= 0 || H <= 0 || W <= 0 || stride <= 0) return -1;
+    const int Ho = scc_oracle_depthwise_out(H, stride), Wo = scc_oracle_depthwise_out(W, stride);
+#pragma omp parallel for schedule(static)
+    for (int a = 0; a < C; ++a) {
+        const double *ka = kdw + (size_t)a * 9;
+        double dk[9] = {0, 0, 0, 0, 0, 0, 0, 0, 0};
+        for (int n = 0; n < N; ++n) {
+            const double *xi = x + ((size_t)n * C + a) * H * W;
+            const double *go = dz + ((size_t)n * C + a) * Ho * Wo;
+            double *gi = dx + ((size_t)n * C + a) * H * W;
+            for (int e = 0; e < H * W; ++e) gi[e] = 0.0;
+            for (int m = 0; m < Ho; ++m) {
+                for (int q = 0; q < Wo; ++q) {
+                    for (int i = 0; i < 3; ++i) {
+                        for (int j = 0; j < 3; ++j) {
+                            int r = stride * m + i - 1, c = stride * q + j - 1;
+                            if (r < 0 || r >= H || c < 0 || c >= W) continue;
+                            gi[(size_t)r * W + c] += ka[i * 3 + j] * go[(size_t)m * Wo + q];
+                            dk[i * 3 + j] += go[(size_t)m * Wo + q] * xi[(size_t)r * W + c];
+                        }
+                    }
+                }
+            }
+        }
+        for (int t = 0; t < 9; ++t) dkdw[(size_t)a * 9 + t] = dk[t];
     }
     return 0;
 }

@@ -47,6 +47,8 @@ def _load():
         lib.scc_oracle_depthwise_out.restype = ctypes.c_int
         lib.scc_oracle_depthwise3x3.argtypes = [dp, dp, dp] + [ctypes.c_int] * 5
         lib.scc_oracle_depthwise3x3.restype = ctypes.c_int
+        lib.scc_oracle_depthwise3x3_backward.argtypes = [dp] * 5 + [ctypes.c_int] * 5
+        lib.scc_oracle_depthwise3x3_backward.restype = ctypes.c_int
         _lib = lib
     return _lib
 
@@ -140,3 +142,15 @@ def depthwise3x3(x, kdw, stride=1):
 def depthwise_scc_forward(x, kdw, w, cg, co, stride=1):
     """The DW + SCC block's forward: the SCC forward of the depthwise stage's output (Section 3.1 on Eq. 2)."""
     return forward(depthwise3x3(x, kdw, stride), w, cg, co)
+
+
+def depthwise3x3_backward(x, kdw, dz, stride=1):
+    """(dx, dkdw): the gradients of depthwise3x3 with respect to its input and its filters, given dz = dL/dz."""
+    x, kdw, dz = _d(x), _d(kdw), _d(dz)
+    N, C, H, W = x.shape
+    assert kdw.shape == (C, 3, 3), "kdw must be [C, 3, 3]"
+    assert dz.shape == (N, C, depthwise_out(H, stride), depthwise_out(W, stride)), "dz must have the shape of the stage's output"
+    dx = np.empty_like(x)
+    dk = np.empty((C, 3, 3), dtype=np.float64)
+    _check(_load().scc_oracle_depthwise3x3_backward(_ptr(x), _ptr(kdw), _ptr(dz), _ptr(dx), _ptr(dk), N, C, H, W, int(stride)))
+    return dx, dk

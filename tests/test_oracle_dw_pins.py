@@ -1,4 +1,5 @@
-"""Pins for the oracle's depthwise 3x3 stage (Eq. 2 of the paper) and for the DW + SCC block's forward.
+"""Pins for the oracle's depthwise 3x3 stage (Eq. 2 of the paper), its two gradients, and the DW + SCC block's
+forward.
 
 The oracle is checked against what Eq. 2 and the mathematics fix, never against itself and never
 against the GPU path: a library grouped convolution, one-tap filters that must be pure shifts, the
@@ -141,3 +142,82 @@ def test_rejects_bad_arguments():
         O.depthwise_out(4, 0)
     with pytest.raises(AssertionError):
         O.depthwise3x3(np.zeros((1, 2, 3, 3)), np.zeros((3, 3, 3)))
+
+
+# ----------------------------------------------------------------------------------------------------------
+# the two gradients of the depthwise stage
+@pytest.mark.parametrize("stride", [1, 2, 3])
+@pytest.mark.parametrize("shape", SHAPES)
+def test_gradients_equal_library_autograd(shape, stride):
+    """torch differentiates its own grouped convolution (fp64): both gradients must agree with it."""
+    N, C, H, W = shape
+    x = torch.from_numpy(draw(shape, 21)).requires_grad_(True)
+    k = torch.from_numpy(draw((C, 3, 3), 22)).requires_grad_(True)
+    z = F.conv2d(x, k.reshape(C, 1, 3, 3), stride=stride, padding=1, groups=C)
+    dz = draw(tuple(z.shape), 23)
+    z.backward(torch.from_numpy(dz))
+    dx, dk = O.depthwise3x3_backward(x.detach().numpy(), k.detach().numpy(), dz, stride)
+    assert np.abs(dx - x.grad.numpy()).max() <= 1e-12 * max(1.0, np.abs(x.grad.numpy()).max())
+    assert np.abs(dk - k.grad.numpy()).max() <= 1e-12 * max(1.0, np.abs(k.grad.numpy()).max())
+
+
+@pytest.mark.parametrize("stride", [1, 2])
+def test_grad_input_is_the_transposed_dense_matrix(stride):
+    """With z = D x (D assembled tap by tap from Eq. 2, separate index code), dx = D^T dz."""
+    N, C, H, W = 1, 2, 5, 4
+    x, k = draw((N, C, H, W), 24), draw((C, 3, 3), 25)
+    Ho, Wo = (H - 1) // stride + 1, (W - 1) // stride + 1
+    D = np.zeros((C * Ho * Wo, C * H * W))
+    for a, m, n, i, j in itertools.product(range(C), range(Ho), range(Wo), range(3), range(3)):
+        r, c = stride * m + i - 1, stride * n + j - 1
+        if 0 <= r < H and 0 <= c < W:
+            D[(a * Ho + m) * Wo + n, (a * H + r) * W + c] += k[a, i, j]
+    dz = draw((N, C, Ho, Wo), 26)
+    dx, _ = O.depthwise3x3_backward(x, k, dz, stride)
+    assert np.abs(dx.reshape(-1) - D.T @ dz.reshape(-1)).max() <= 1e-13
+
+
+@pytest.mark.parametrize("stride", [1, 2])
+def test_adjoint_identities(stride):
+    """<dz, DW(x; k)> = <dx, x> = <dk, k>: the stage is linear in x and in k, so both gradients pair back to it."""
+    x, k = draw((3, 4, 6, 7), 27), draw((4, 3, 3), 28)
+    z = O.depthwise3x3(x, k, stride)
+    dz = draw(z.shape, 29)
+    dx, dk = O.depthwise3x3_backward(x, k, dz, stride)
+    lhs = float((dz * z).sum())
+    assert abs(lhs - float((dx * x).sum())) <= 1e-10 * abs(lhs)
+    assert abs(lhs - float((dk * k).sum())) <= 1e-10 * abs(lhs)
+
+
+def test_gradients_by_central_differences():
+    x, k = draw((2, 2, 4, 5), 30), draw((2, 3, 3), 31)
+    dz = draw(O.depthwise3x3(x, k, 2).shape, 32)
+    dx, dk = O.depthwise3x3_backward(x, k, dz, 2)
+    loss = lambda xx, kk: float((O.depthwise3x3(xx, kk, 2) * dz).sum())
+    h = 1e-5
+    for idx in [(0, 0, 0, 0), (1, 1, 3, 4), (0, 1, 2, 2)]:
+        xp, xm = x.copy(), x.copy()
+        xp[idx] += h
+        xm[idx] -= h
+        assert abs((loss(xp, k) - loss(xm, k)) / (2 * h) - dx[idx]) <= 1e-8
+    for idx in [(0, 0, 0), (1, 2, 2), (0, 1, 2)]:
+        kp, km = k.copy(), k.copy()
+        kp[idx] += h
+        km[idx] -= h
+        assert abs((loss(x, kp) - loss(x, km)) / (2 * h) - dk[idx]) <= 1e-8
+
+
+def test_grad_of_single_tap_filter_is_the_opposite_shift():
+    """Tap (i, j) alone moves pixel (m+i-1, n+j-1) to (m, n); its grad-input moves dz(m, n) back to (m+i-1, n+j-1)."""
+    dz = draw((1, 1, 5, 6), 33)
+    for i, j in itertools.product(range(3), range(3)):
+        k = np.zeros((1, 3, 3))
+        k[0, i, j] = 1.0
+        dx, dk = O.depthwise3x3_backward(np.zeros((1, 1, 5, 6)), k, dz, 1)
+        want = np.zeros((5, 6))
+        for m in range(5):
+            for n in range(6):
+                r, c = m + i - 1, n + j - 1
+                if 0 <= r < 5 and 0 <= c < 6:
+                    want[r, c] = dz[0, 0, m, n]
+        assert np.array_equal(dx[0, 0], want) and not dk.any()
