@@ -171,6 +171,24 @@ int scc_depthwise3x3_forward(const void* x, const void* kdw, void* z,
                              int N, int C, int H, int W, int dw_stride, scc_dtype dtype, void* stream);
 
 /*
+ * Gradients of the depthwise 3x3 stage (the derivatives of Eq. 2; the paper trains DW + SCC blocks end to end
+ * and gives no formula for them).  With dz the gradient of the loss with respect to the stage's output z:
+ *     dx[n,a,r,c]   = sum over taps (i,j) and outputs (m,q) with s*m+i-1 = r, s*q+j-1 = c of kdw[a,i,j] * dz[n,a,m,q]
+ *     dkdw[a,i,j]   = sum_{n,m,q} dz[n,a,m,q] * x[n,a, s*m+i-1, s*q+j-1]        (pixels outside the map: zero)
+ * x: in, N*C*H*W (needed for dkdw).  kdw: in, C*9 (needed for dx).  dz: in, N*C*Ho*Wo.  dx: out, N*C*H*W, dtype of x.
+ * dkdw: out, C*9 binary32 values in BOTH dtypes.  Either of dx, dkdw may be NULL: that gradient is skipped (and the
+ * input only it needs may be NULL too).  Sums are binary32; dkdw is summed in a fixed order (per thread, per
+ * workgroup, then over slices of the batch), so two calls give bitwise identical results.  workspace: device
+ * scratch of at least scc_depthwise3x3_backward_workspace_bytes(...) bytes when dkdw is wanted, 256-byte aligned,
+ * owned by the caller, contents undefined before and after; may be NULL when the query returns 0.
+ * Errors: SCC_ERR_NULL, SCC_ERR_SHAPE, SCC_ERR_DTYPE, SCC_ERR_WORKSPACE, SCC_ERR_LAUNCH.
+ */
+size_t scc_depthwise3x3_backward_workspace_bytes(int N, int C, int H, int W, int dw_stride, scc_dtype dtype);
+int scc_depthwise3x3_backward(const void* x, const void* kdw, const void* dz, void* dx, void* dkdw,
+                              int N, int C, int H, int W, int dw_stride, scc_dtype dtype,
+                              void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Forward of a whole DW + SCC block (Section 3.1: the SCC takes the place of the pointwise convolution
  * behind the depthwise one of Eq. 2):
  *     y = scc_forward(scc_depthwise3x3_forward(x, kdw), w)

@@ -258,6 +258,37 @@ int scc_depthwise3x3_forward(const void* x, const void* kdw, void* z, int N, int
                                                   g, (hipStream_t)stream));
 }
 
+size_t scc_depthwise3x3_backward_workspace_bytes(int N, int C, int H, int W, int dw_stride, scc_dtype dtype)
+{
+    scc::DwGeom g;
+    if (N <= 0 || make_dw_geom(C, H, W, dw_stride, &g) != SCC_OK || !dtype_ok(dtype)) return 0;
+    return scc::depthwise3x3_backward_workspace(N, C, g);
+}
+
+int scc_depthwise3x3_backward(const void* x, const void* kdw, const void* dz, void* dx, void* dkdw, int N, int C, int H,
+                              int W, int dw_stride, scc_dtype dtype, void* workspace, size_t workspace_bytes,
+                              void* stream)
+{
+    if (!dz || (!dx && !dkdw) || (dx && !kdw) || (dkdw && !x)) return SCC_ERR_NULL;
+    scc::DwGeom g;
+    if (N <= 0) return SCC_ERR_SHAPE;
+    const int rc = make_dw_geom(C, H, W, dw_stride, &g);
+    if (rc != SCC_OK) return rc;
+    if ((long long)N * H * W > std::numeric_limits<int>::max()) return SCC_ERR_SHAPE;
+    if (!dtype_ok(dtype)) return SCC_ERR_DTYPE;
+    const size_t need = dkdw ? scc::depthwise3x3_backward_workspace(N, C, g) : 0;
+    if (need > 0 && (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 255u) != 0))
+        return SCC_ERR_WORKSPACE;
+    drop_stale_error();
+    if (dtype == SCC_F32)
+        return launch_status(scc::launch_depthwise3x3_backward((const float*)x, (const float*)kdw, (const float*)dz,
+                                                               (float*)dx, (float*)dkdw, (float*)workspace, N, C, g,
+                                                               (hipStream_t)stream));
+    return launch_status(scc::launch_depthwise3x3_backward((const scc::bf16_t*)x, (const scc::bf16_t*)kdw,
+                                                           (const scc::bf16_t*)dz, (scc::bf16_t*)dx, (float*)dkdw,
+                                                           (float*)workspace, N, C, g, (hipStream_t)stream));
+}
+
 // Problem of the SCC behind the depthwise stage (it sees the Ho x Wo map) and the stage's geometry.
 static int make_dw_problem(int N, int Cin, int Cout, int H, int W, int dw_stride, int cg, double co, Problem* p,
                            scc::DwGeom* g)

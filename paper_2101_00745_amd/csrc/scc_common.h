@@ -124,8 +124,17 @@ hipError_t launch_backward_merged(const T* x, const T* dy, const T* w, T* dx, fl
                                   const Problem& p, hipStream_t st);
 
 // Depthwise 3x3 stage and the fused DW + SCC forward (scc_dw_fwd.hip); `p` describes the SCC on the Ho x Wo map
+// flip: the filters turned by 180 degrees (tap (i, j) takes the weight of tap (2-i, 2-j)): at stride 1 that is the
+// stage's gradient with respect to its input, applied to dz
 template <typename T>
-hipError_t launch_depthwise3x3(const T* x, const T* kdw, T* z, int N, int C, const DwGeom& g, hipStream_t st);
+hipError_t launch_depthwise3x3(const T* x, const T* kdw, T* z, int N, int C, const DwGeom& g, hipStream_t st,
+                               bool flip = false);
+
+// Gradients of the depthwise stage (scc_dw_bwd.hip).  dx and dk may each be null (that gradient is skipped).
+size_t depthwise3x3_backward_workspace(int N, int C, const DwGeom& g);
+template <typename T>
+hipError_t launch_depthwise3x3_backward(const T* x, const T* kdw, const T* dz, T* dx, float* dk, float* workspace, int N,
+                                        int C, const DwGeom& g, hipStream_t st);
 bool dw_forward_fused_eligible(const Problem& p);    // the fused kernel can run the layer
 bool dw_forward_fused_preferred(const Problem& p);   // ... and is the faster path for it
 hipError_t launch_dw_forward_fused(const float* x, const float* kdw, const float* w, float* y, const Problem& p,

@@ -11,10 +11,13 @@
 // per 16 channels, binary32 sums), like the stand-alone forward.  HBM sees x once and y once.
 #include "scc_band.h"
 #include "scc_common.h"
+#include "scc_dw_strip.h"
 
 namespace scc {
 
 namespace {
+
+using dw::dw_strip;
 
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
@@ -38,72 +41,12 @@ int pow2_floor_dw(int v)
     return p;
 }
 
-// ---------------------------------------------------------------------------------------------------------
-// A strip: RB consecutive output rows x 4 consecutive output columns of one channel, for spatial stride S (1 or 2).
-// It reads NR = S*(RB-1)+3 input rows, each once: 4*S pixels from the strip's first input column on (one or two
-// 16-byte loads for binary32).  The pixel left of them and, for S == 1, the pixel right of them are the last and
-// first pixel of what the NEIGHBOURING LANES loaded for the same row: lane l-1 must own the strip to the left and
-// lane l+1 the strip to the right (same channel, same rows) whenever `left` / `right` is set and `lo` / `hi` is
-// not; they are fetched with a lane shuffle (single misaligned 4-byte loads measured 40 % of the whole stage).
-//   xc       input pixel (S*r0, S*cw) of the channel: centre of the strip's first output
-//   W        pixels per input row
-//   rowmask  bit t set: input row S*r0 - 1 + t lies inside the map (bit 1 always is)
-//   left     the input column left of the strip exists; right (S == 1): the column right of it exists
-//   lo, hi   the lane has no lane below / above it in the wavefront that owns the neighbouring strip: it loads
-//            the edge pixel itself
-// Rows and columns outside the map are read at an address inside it and replaced by zero.  Every lane of the
-// wavefront must call this together (the shuffles are wavefront-wide).
-template <int S, int RB, typename T_>
-__device__ __forceinline__ void dw_strip(const T_* xc, int W, const float (&k)[9], uint32_t rowmask, bool left, bool right,
-                                         bool lo, bool hi, float (&out)[RB][4])
-{
-    typedef T_ tvec __attribute__((ext_vector_type(4)));
-    constexpr int NR = S * (RB - 1) + 3;
-#pragma unroll
-    for (int rr = 0; rr < RB; ++rr)
-#pragma unroll
-        for (int i = 0; i < 4; ++i) out[rr][i] = 0.f;
-#pragma unroll
-    for (int t = 0; t < NR; ++t) {
-        const bool ok = (rowmask >> t) & 1u;
-        const T_* row = ok ? xc + (t - 1) * W : xc;
-        float v[4 * S + 2];
-        float raw[4 * S];
-#pragma unroll
-        for (int h = 0; h < S; ++h) {
-            const tvec m = *(const tvec*)(row + 4 * h);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) raw[4 * h + e] = to_f32(m[e]);
-        }
-        float lv = __shfl_up(raw[4 * S - 1], 1, 64);
-        if (lo && left) lv = to_f32(row[-1]);
-        v[0] = (ok && left) ? lv : 0.f;
-#pragma unroll
-        for (int e = 0; e < 4 * S; ++e) v[1 + e] = ok ? raw[e] : 0.f;
-        if constexpr (S == 1) {
-            float rv = __shfl_down(raw[0], 1, 64);
-            if (hi && right) rv = to_f32(row[4]);
-            v[5] = (ok && right) ? rv : 0.f;
-        } else {
-            v[4 * S + 1] = 0.f;   // never used: the last tap of the last output reads v[S*3 + 2] = v[8]
-        }
-#pragma unroll
-        for (int rr = 0; rr < RB; ++rr) {
-            const int di = t - S * rr;   // tap row of output row rr that this input row feeds
-            if (di < 0 || di > 2) continue;
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-#pragma unroll
-                for (int j = 0; j < 3; ++j) out[rr][i] += k[di * 3 + j] * v[S * i + j];
-        }
-    }
-}
-
 // Stand-alone depthwise stage on strips (see dw_strip): stride 1 or 2 with output rows that are a multiple of 4
 // pixels, input maps of exactly S times the output size, RB dividing the output rows, tensors aligned to 4 values.
 template <typename T_, int S, int RB>
 __global__ __launch_bounds__(256) void depthwise3x3_strips(const T_* __restrict__ x, const T_* __restrict__ kdw,
-                                                           T_* __restrict__ z, int C, DwGeom G, long long items)
+                                                           T_* __restrict__ z, int C, DwGeom G, long long items,
+                                                           int flip)
 {
     typedef T_ tvec __attribute__((ext_vector_type(4)));
     const size_t HWi = (size_t)G.H * G.W, HWo = (size_t)G.Ho * G.Wo;
@@ -123,10 +66,8 @@ __global__ __launch_bounds__(256) void depthwise3x3_strips(const T_* __restrict_
         const int a = (int)(t % (uint32_t)C);
         float k[9];
 #pragma unroll
-        for (int i = 0; i < 9; ++i) k[i] = to_f32(kdw[a * 9 + i]);
-        uint32_t rowmask = (1u << (S * (RB - 1) + 3)) - 1;
-        if (r0 == 0) rowmask &= ~1u;
-        if (S == 1 && r0 + RB == G.Ho) rowmask &= ~(1u << (RB + 1));
+        for (int i = 0; i < 9; ++i) k[i] = to_f32(kdw[a * 9 + (flip ? 8 - i : i)]);   // flip: the filter turned by 180 degrees
+        const uint32_t rowmask = dw::strip_rowmask<S, RB>(r0, G.Ho);
         float out[RB][4];
         // consecutive strips of a row are consecutive lanes; the first and last lane of the wavefront and the
         // last live one have no neighbour to ask
@@ -147,7 +88,8 @@ __global__ __launch_bounds__(256) void depthwise3x3_strips(const T_* __restrict_
 // Stand-alone depthwise stage, any stride and map size: one thread per output value, taps in row-major order.
 template <typename T_>
 __global__ __launch_bounds__(256) void depthwise3x3_kernel(const T_* __restrict__ x, const T_* __restrict__ kdw,
-                                                           T_* __restrict__ z, int C, DwGeom G, long long items)
+                                                           T_* __restrict__ z, int C, DwGeom G, long long items,
+                                                           int flip)
 {
     const long long HWi = (long long)G.H * G.W;
     for (long long e = (long long)blockIdx.x * 256 + threadIdx.x; e < items; e += (long long)gridDim.x * 256) {
@@ -166,7 +108,7 @@ __global__ __launch_bounds__(256) void depthwise3x3_kernel(const T_* __restrict_
             for (int j = 0; j < 3; ++j) {
                 const int cc = G.s * q + j - 1;
                 if (cc < 0 || cc >= G.W) continue;
-                out += to_f32(kdw[a * 9 + i * 3 + j]) * to_f32(xc[(long long)rr * G.W + cc]);
+                out += to_f32(kdw[a * 9 + (flip ? 8 - (i * 3 + j) : i * 3 + j)]) * to_f32(xc[(long long)rr * G.W + cc]);
             }
         }
         z[e] = from_f32<T_>(out);
@@ -280,10 +222,7 @@ __global__ __launch_bounds__(256) void dw_scc_forward_lds(const float* __restric
         const long long qs = live ? qa : 0;
         const int n = (int)(qs / P.HW), r0 = (int)(qs % P.HW) / G.Wo;
         const float* xb = x + (size_t)n * P.Cin * HWi + (size_t)(S * r0) * G.W + S * cw;
-        uint32_t rowmask = (1u << (S * (RB - 1) + 3)) - 1;
-        if (r0 == 0) rowmask &= ~1u;
-        if (S == 1 && r0 + RB == G.Ho) rowmask &= ~(1u << (RB + 1));
-        if (!live) rowmask = 0;
+        const uint32_t rowmask = live ? dw::strip_rowmask<S, RB>(r0, G.Ho) : 0u;
         const bool left = cw > 0, right = cw + 4 < G.Wo;
         const int colbase = srow * G.Wo + cw;    // column of the strip's first output inside the tile
 #pragma unroll 2
@@ -493,7 +432,7 @@ hipError_t launch_fused_cp(const float* x, const float* kdw, const float* w, flo
 }
 
 template <typename T, int S>
-hipError_t launch_strips(const T* x, const T* kdw, T* z, int N, int C, const DwGeom& g, hipStream_t st)
+hipError_t launch_strips(const T* x, const T* kdw, T* z, int N, int C, const DwGeom& g, hipStream_t st, int flip)
 {
     // taller strips read fewer halo rows per output; small problems take shorter ones to have enough threads
     int rb = g.Ho % 4 == 0 ? 4 : g.Ho % 2 == 0 ? 2 : 1;
@@ -503,33 +442,35 @@ hipError_t launch_strips(const T* x, const T* kdw, T* z, int N, int C, const DwG
     if (blocks > (1ll << 20)) blocks = 1ll << 20;   // the kernel strides over what is left
     const dim3 grid((unsigned)blocks), block(256);
     if (rb == 4)
-        depthwise3x3_strips<T, S, 4><<<grid, block, 0, st>>>(x, kdw, z, C, g, items);
+        depthwise3x3_strips<T, S, 4><<<grid, block, 0, st>>>(x, kdw, z, C, g, items, flip);
     else if (rb == 2)
-        depthwise3x3_strips<T, S, 2><<<grid, block, 0, st>>>(x, kdw, z, C, g, items);
+        depthwise3x3_strips<T, S, 2><<<grid, block, 0, st>>>(x, kdw, z, C, g, items, flip);
     else
-        depthwise3x3_strips<T, S, 1><<<grid, block, 0, st>>>(x, kdw, z, C, g, items);
+        depthwise3x3_strips<T, S, 1><<<grid, block, 0, st>>>(x, kdw, z, C, g, items, flip);
     return hipGetLastError();
 }
 
 }  // namespace
 
 template <typename T>
-hipError_t launch_depthwise3x3(const T* x, const T* kdw, T* z, int N, int C, const DwGeom& g, hipStream_t st)
+hipError_t launch_depthwise3x3(const T* x, const T* kdw, T* z, int N, int C, const DwGeom& g, hipStream_t st, bool flip)
 {
     const bool strips = (g.s == 1 || g.s == 2) && g.Wo % 4 == 0 && g.H == g.s * g.Ho && g.W == g.s * g.Wo &&
                         (((uintptr_t)x | (uintptr_t)z) & (4 * sizeof(T) - 1)) == 0 &&
                         (long long)N * C * g.Ho * (g.Wo / 4) < (1ll << 31);
-    if (strips) return g.s == 1 ? launch_strips<T, 1>(x, kdw, z, N, C, g, st) : launch_strips<T, 2>(x, kdw, z, N, C, g, st);
+    if (strips)
+        return g.s == 1 ? launch_strips<T, 1>(x, kdw, z, N, C, g, st, flip) : launch_strips<T, 2>(x, kdw, z, N, C, g, st, flip);
     const long long items = (long long)N * C * g.Ho * g.Wo;
     long long blocks = (items + 255) / 256;
     if (blocks > (1ll << 20)) blocks = 1ll << 20;
-    depthwise3x3_kernel<T><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(x, kdw, z, C, g, items);
+    depthwise3x3_kernel<T><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(x, kdw, z, C, g, items, flip);
     return hipGetLastError();
 }
 
-template hipError_t launch_depthwise3x3<float>(const float*, const float*, float*, int, int, const DwGeom&, hipStream_t);
+template hipError_t launch_depthwise3x3<float>(const float*, const float*, float*, int, int, const DwGeom&, hipStream_t,
+                                               bool);
 template hipError_t launch_depthwise3x3<bf16_t>(const bf16_t*, const bf16_t*, bf16_t*, int, int, const DwGeom&,
-                                                hipStream_t);
+                                                hipStream_t, bool);
 
 // The fused kernel takes layers whose channel count is a multiple of 16 (a 16-channel chunk of the matrix
 // instruction then never straddles the cyclic wrap) and whose z tile of 32 columns fits 144 KiB of LDS.

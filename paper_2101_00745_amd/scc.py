@@ -17,7 +17,8 @@ SCC_F32, SCC_BF16 = 0, 1
 SYMBOLS = ("scc_window_params", "scc_forward", "scc_backward_input",
            "scc_backward_weight_workspace_bytes", "scc_backward_weight", "scc_backward_weight_static",
            "scc_backward_workspace_bytes", "scc_backward",
-           "scc_depthwise3x3_out", "scc_depthwise3x3_forward", "scc_dw_forward_workspace_bytes", "scc_dw_forward_fusable", "scc_dw_forward",
+           "scc_depthwise3x3_out", "scc_depthwise3x3_forward", "scc_depthwise3x3_backward_workspace_bytes",
+           "scc_depthwise3x3_backward", "scc_dw_forward_workspace_bytes", "scc_dw_forward_fusable", "scc_dw_forward",
            "scc_status_string")
 STATIC_SCRATCH_BYTES = 8 << 20    # SCC_STATIC_SCRATCH_BYTES of include/scc.h
 
@@ -62,6 +63,10 @@ def load():
     lib.scc_depthwise3x3_out.restype = c_int
     lib.scc_depthwise3x3_forward.argtypes = [c_vp, c_vp, c_vp] + [c_int] * 6 + [c_vp]
     lib.scc_depthwise3x3_forward.restype = c_int
+    lib.scc_depthwise3x3_backward_workspace_bytes.argtypes = [c_int] * 6
+    lib.scc_depthwise3x3_backward_workspace_bytes.restype = c_sz
+    lib.scc_depthwise3x3_backward.argtypes = [c_vp] * 5 + [c_int] * 6 + [c_vp, c_sz, c_vp]
+    lib.scc_depthwise3x3_backward.restype = c_int
     dw_shape = [c_int] * 7 + [c_dbl, c_int]     # N, Cin, Cout, H, W, dw_stride, cg, co, dtype
     lib.scc_dw_forward_workspace_bytes.argtypes = dw_shape
     lib.scc_dw_forward_workspace_bytes.restype = c_sz
@@ -251,6 +256,39 @@ def scc_depthwise3x3_forward(x, kdw, dw_stride=1, out=None):
         _check(load().scc_depthwise3x3_forward(x.data_ptr(), kdw.data_ptr(), z.data_ptr(), N, C, H, W, int(dw_stride),
                                                _dtype_code(x), _stream(dev)))
     return z
+
+
+def scc_depthwise3x3_backward(x, kdw, dz, dw_stride=1, need_dx=True, need_dk=True, out_dx=None, out_dk=None,
+                              workspace=None):
+    """(dx, dkdw) of the depthwise 3x3 stage: x [N,C,H,W], kdw [C,3,3], dz [N,C,Ho,Wo] -> dx like x, dkdw [C,3,3] float32.
+    A gradient that is not needed comes back as None."""
+    dev = _dev(x, kdw, dz)
+    N, C, H, W = x.shape
+    Ho, Wo = scc_depthwise3x3_out(H, dw_stride), scc_depthwise3x3_out(W, dw_stride)
+    if kdw.dtype != x.dtype or tuple(kdw.shape) != (C, 3, 3):
+        raise ValueError("kdw must be [C, 3, 3] with the dtype of x")
+    if dz.dtype != x.dtype or tuple(dz.shape) != (N, C, Ho, Wo):
+        raise ValueError("dz must be [N, C, Ho, Wo] with the dtype of x")
+    if not (need_dx or need_dk):
+        return None, None
+    code = _dtype_code(x)
+    need = int(load().scc_depthwise3x3_backward_workspace_bytes(N, C, H, W, int(dw_stride), code)) if need_dk else 0
+    if workspace is None and need > 0:
+        workspace = torch.empty(need, dtype=torch.uint8, device=dev)
+    dx = (torch.empty_like(x) if out_dx is None else out_dx) if need_dx else None
+    dk = (torch.empty((C, 3, 3), dtype=torch.float32, device=dev) if out_dk is None else out_dk) if need_dk else None
+    for o, shp, dt in ((out_dx, x.shape, x.dtype), (out_dk, (C, 3, 3), torch.float32)):
+        if o is not None:
+            _dev(o)
+            assert o.shape == shp and o.dtype == dt
+    ws_ptr = workspace.data_ptr() if workspace is not None else None
+    ws_len = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    with torch.cuda.device(dev):
+        _check(load().scc_depthwise3x3_backward(x.data_ptr(), kdw.data_ptr(), dz.data_ptr(),
+                                                dx.data_ptr() if dx is not None else None,
+                                                dk.data_ptr() if dk is not None else None, N, C, H, W, int(dw_stride),
+                                                code, ws_ptr, ws_len, _stream(dev)))
+    return dx, dk
 
 
 def scc_dw_forward_workspace_bytes(N, Cin, Cout, H, W, dw_stride, cg, co, dtype=torch.float32):

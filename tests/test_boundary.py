@@ -158,6 +158,19 @@ def test_dw_block_null_pointers_and_workspace():
     assert lib.scc_dw_forward_fusable(*shape) == 0 and lib.scc_dw_forward_fusable(128, 256, 256, 16, 16, 1, 4, 0.5, 1) == 0
     assert lib.scc_dw_forward_fusable(128, 256, 256, 16, 16, 0, 4, 0.5, 0) == -2
     assert lib.scc_dw_forward_fusable(128, 256, 256, 16, 16, 1, 4, 0.5, 7) == -4
+    # the depthwise stage's gradients: dz is required, at least one output, and the input each output needs
+    args = (2, 8, 5, 5, 1, 0)
+    need = lib.scc_depthwise3x3_backward_workspace_bytes(*args)
+    assert need == 2 * 8 * 9 * 4                  # two slices of the batch x 8 channels x 9 taps
+    assert lib.scc_depthwise3x3_backward(FAKE, FAKE, None, FAKE, FAKE, *args, FAKE, need, None) == -1
+    assert lib.scc_depthwise3x3_backward(FAKE, FAKE, FAKE, None, None, *args, FAKE, need, None) == -1
+    assert lib.scc_depthwise3x3_backward(None, FAKE, FAKE, FAKE, FAKE, *args, FAKE, need, None) == -1    # dkdw needs x
+    assert lib.scc_depthwise3x3_backward(FAKE, None, FAKE, FAKE, FAKE, *args, FAKE, need, None) == -1    # dx needs kdw
+    assert lib.scc_depthwise3x3_backward(FAKE, FAKE, FAKE, FAKE, FAKE, *args, None, 0, None) == -5
+    assert lib.scc_depthwise3x3_backward(FAKE, FAKE, FAKE, FAKE, FAKE, *args, FAKE, need - 1, None) == -5
+    assert lib.scc_depthwise3x3_backward(FAKE, FAKE, FAKE, FAKE, FAKE, 2, 8, 5, 5, 0, 0, FAKE, need, None) == -2
+    assert lib.scc_depthwise3x3_backward(FAKE, FAKE, FAKE, FAKE, FAKE, 2, 8, 5, 5, 1, 3, FAKE, need, None) == -4
+    assert lib.scc_depthwise3x3_backward_workspace_bytes(0, 8, 5, 5, 1, 0) == 0
     assert lib.scc_depthwise3x3_out(32, 2) == 16 and lib.scc_depthwise3x3_out(7, 2) == 4
     assert lib.scc_depthwise3x3_out(0, 1) == -2 and lib.scc_depthwise3x3_out(5, 0) == -2
 

@@ -222,3 +222,91 @@ def test_output_buffer_is_fully_overwritten(S):
     torch.cuda.synchronize()
     assert not torch.isnan(out).any() and torch.isnan(buf[n:]).all()
     assert rel_err(host(out), O.depthwise_scc_forward(xin, kdw, w, layer.cg, layer.co, 1)) <= 2e-5
+
+
+# ------------------------------------------------------------------------------------- gradients of the depthwise stage
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("dw_stride", [1, 2, 3])
+@pytest.mark.parametrize("shape", DW_SHAPES + [(70, 40, 8, 8), (3, 300, 4, 4), (33, 16, 16, 12)])
+def test_depthwise_stage_gradients(S, shape, dw_stride, dtype):
+    """dx and dkdw against the oracle.  dkdw is binary32 in both dtypes (sums of exact products of the values both
+    sides see), so it is held to 2e-5 for bf16 inputs too."""
+    N, C, H, W = shape
+    rng = np.random.default_rng(7450900 + 13 * H + W + 100 * dw_stride + N)
+    x = rng.standard_normal(shape).astype(np.float32)
+    k = (rng.standard_normal((C, 3, 3)) / 3.0).astype(np.float32)
+    Ho, Wo = (H - 1) // dw_stride + 1, (W - 1) // dw_stride + 1
+    dz = rng.standard_normal((N, C, Ho, Wo)).astype(np.float32)
+    xd, kd, dzd = to_dev(x, dtype), to_dev(k, dtype), to_dev(dz, dtype)
+    dx, dk = S.scc_depthwise3x3_backward(xd, kd, dzd, dw_stride)
+    torch.cuda.synchronize()
+    ref_dx, ref_dk = O.depthwise3x3_backward(host(xd), host(kd), host(dzd), dw_stride)
+    assert dx.dtype == dtype and dk.dtype == torch.float32 and tuple(dk.shape) == (C, 3, 3)
+    assert rel_err(host(dx), ref_dx) <= TOL[dtype]
+    assert rel_err(host(dk), ref_dk) <= 2e-5
+
+
+def test_depthwise_stage_gradients_full_size_and_repeatable(S):
+    """The metric layer's depthwise stage at full size (the oracle runs on a few channels of it: channels never mix),
+    twice: bitwise equal results, and one gradient at a time gives the same values."""
+    layer = Wk.METRIC
+    xin, kdw, _ = Wk.make_block_inputs(layer, 1)
+    dz = np.random.default_rng(7450999).standard_normal(xin.shape).astype(np.float32)
+    xd, kd, dzd = (to_dev(a, torch.float32) for a in (xin, kdw, dz))
+    dx1, dk1 = S.scc_depthwise3x3_backward(xd, kd, dzd, 1)
+    dx2, dk2 = S.scc_depthwise3x3_backward(xd, kd, dzd, 1)
+    dx3, none = S.scc_depthwise3x3_backward(xd, kd, dzd, 1, need_dk=False)
+    none2, dk3 = S.scc_depthwise3x3_backward(xd, kd, dzd, 1, need_dx=False)
+    torch.cuda.synchronize()
+    assert torch.equal(dx1, dx2) and torch.equal(dk1, dk2) and torch.equal(dx1, dx3) and torch.equal(dk1, dk3)
+    assert none is None and none2 is None
+    pick = [0, 97, 255]
+    ref_dx, ref_dk = O.depthwise3x3_backward(xin[:, pick], kdw[pick], dz[:, pick], 1)
+    assert rel_err(host(dx1[:, pick]), ref_dx) <= 2e-5 and rel_err(host(dk1[pick]), ref_dk) <= 2e-5
+
+
+@pytest.mark.parametrize("cfg", [(6, 32, 48, 8, 8, 2, 0.5, 1), (5, 64, 64, 6, 6, 4, 0.5, 2), (4, 24, 40, 5, 7, 2, 0.5, 1),
+                                 (128, 32, 64, 16, 16, 2, 0.5, 2)])
+def test_block_module_autograd_matches_oracle(S, cfg):
+    """DWSCCBlock end to end: y, dx, the depthwise filters' gradient and the SCC weights' gradient against the oracle's
+    composition (forward: DW then SCC; backward: SCC grads on the DW output, then the DW grads on dz)."""
+    from paper_2101_00745_amd.nn import DWSCCBlock
+    N, Cin, Cout, H, W, cg, co, s = cfg
+    layer = layer_of(N, Cin, Cout, H, W, cg, co, idx=3)
+    xin, kdw, w = Wk.make_block_inputs(layer, s)
+    dy = np.random.default_rng(7450777).standard_normal((N, Cout, H, W)).astype(np.float32)
+    m = DWSCCBlock(Cin, Cout, cg=cg, co=co, stride=s)
+    with torch.no_grad():
+        m.dw_weight.copy_(torch.from_numpy(kdw))
+        m.weight.copy_(torch.from_numpy(w))
+    xd = torch.from_numpy(xin).cuda().requires_grad_(True)
+    y = m(xd)
+    y.backward(torch.from_numpy(dy).cuda())
+    torch.cuda.synchronize()
+    z = O.depthwise3x3(xin, kdw, s)
+    assert rel_err(host(y.detach()), O.forward(z, w, cg, co)) <= 2e-5
+    dz = O.backward_input(dy, w, Cin, cg, co)
+    ref_dx, ref_dk = O.depthwise3x3_backward(xin, kdw, dz, s)
+    assert rel_err(host(xd.grad), ref_dx) <= 2e-5
+    assert rel_err(host(m.dw_weight.grad), ref_dk) <= 2e-5
+    assert rel_err(host(m.weight.grad), O.backward_weight(z, dy, cg, co)) <= 2e-5
+
+
+def test_block_module_trains(S):
+    """A student DWSCCBlock fitted to a teacher of the same shape, all arithmetic of the block in the library's
+    kernels: the loss must fall."""
+    from paper_2101_00745_amd.nn import DWSCCBlock
+    torch.manual_seed(0)
+    teacher, student = DWSCCBlock(32, 64, cg=2, co=0.5, bias=True), DWSCCBlock(32, 64, cg=2, co=0.5, bias=True)
+    x = torch.randn(16, 32, 8, 8, device="cuda")
+    with torch.no_grad():
+        target = teacher(x)
+    opt = torch.optim.Adam(student.parameters(), lr=0.02)
+    losses = []
+    for _ in range(60):
+        opt.zero_grad()
+        loss = torch.nn.functional.mse_loss(student(x), target)
+        loss.backward()
+        opt.step()
+        losses.append(float(loss.detach()))
+    assert losses[-1] < 0.5 * losses[0], losses[::10]
