@@ -48,6 +48,49 @@ __global__ __launch_bounds__(256) void depthwise3x3_backward_input_gather(const 
     }
 }
 
+// ---- grad-input at stride 2 on even maps (H = 2*Ho, W = 2*Wo, Wo even, tensors aligned to 4 values): the taps
+// that reach input pixel (r, c) are fixed by the parities of r and c, so a thread writes the 2 x 4 input pixels
+// under two neighbouring outputs (m, q0), (m, q0+1) from the 2 x 3 outputs around them:
+//   dx[2m  ][2q  ] = k11*g[m][q]                      dx[2m  ][2q+1] = k10*g[m][q+1] + k12*g[m][q]
+//   dx[2m+1][2q  ] = k01*g[m+1][q] + k21*g[m][q]      dx[2m+1][2q+1] = k00*g[m+1][q+1] + k02*g[m+1][q] + k20*g[m][q+1] + k22*g[m][q]
+template <typename T_>
+__global__ __launch_bounds__(256) void depthwise3x3_backward_input_s2(const T_* __restrict__ dz, const T_* __restrict__ kdw,
+                                                                      T_* __restrict__ dx, int C, DwGeom G, uint32_t items)
+{
+    typedef T_ tvec __attribute__((ext_vector_type(4)));
+    typedef T_ tvec2 __attribute__((ext_vector_type(2)));
+    const uint32_t W2 = G.Wo / 2;
+    const size_t HWi = (size_t)G.H * G.W, HWo = (size_t)G.Ho * G.Wo;
+    for (uint32_t e = blockIdx.x * 256u + threadIdx.x; e < items; e += gridDim.x * 256u) {
+        const int q0 = (int)(e % W2) * 2;
+        uint32_t t = e / W2;
+        const int m = (int)(t % (uint32_t)G.Ho);
+        t /= (uint32_t)G.Ho;                        // t = n*C + a
+        const int a = (int)(t % (uint32_t)C);
+        float k[9];
+#pragma unroll
+        for (int i = 0; i < 9; ++i) k[i] = to_f32(kdw[a * 9 + i]);
+        const T_* g0 = dz + t * HWo + (size_t)m * G.Wo + q0;
+        const bool down = m + 1 < G.Ho, right = q0 + 2 < G.Wo;
+        const T_* g1 = down ? g0 + G.Wo : g0;
+        const tvec2 a01 = *(const tvec2*)g0, b01 = *(const tvec2*)g1;
+        const float a2 = right ? to_f32(g0[2]) : 0.f, b2raw = to_f32(g1[right ? 2 : 0]);
+        const float ga[3] = {to_f32(a01[0]), to_f32(a01[1]), a2};
+        const float gb[3] = {down ? to_f32(b01[0]) : 0.f, down ? to_f32(b01[1]) : 0.f, (down && right) ? b2raw : 0.f};
+        tvec r0, r1;
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            r0[2 * j] = from_f32<T_>(k[4] * ga[j]);
+            r0[2 * j + 1] = from_f32<T_>(k[3] * ga[j + 1] + k[5] * ga[j]);
+            r1[2 * j] = from_f32<T_>(k[1] * gb[j] + k[7] * ga[j]);
+            r1[2 * j + 1] = from_f32<T_>(k[0] * gb[j + 1] + k[2] * gb[j] + k[6] * ga[j + 1] + k[8] * ga[j]);
+        }
+        T_* o = dx + t * HWi + (size_t)(2 * m) * G.W + 2 * q0;
+        __builtin_nontemporal_store(r0, (tvec*)o);
+        __builtin_nontemporal_store(r1, (tvec*)(o + G.W));
+    }
+}
+
 // ---- grad-filter ----------------------------------------------------------------------------------------------
 constexpr int kDkThreads = 256;
 
@@ -206,6 +249,15 @@ hipError_t launch_depthwise3x3_backward(const T* x, const T* kdw, const T* dz, T
             // the stage applied to dz (an Ho x Wo = H x W map) with the filters turned by 180 degrees
             DwGeom gz = g;
             const hipError_t e = launch_depthwise3x3(dz, kdw, dx, N, C, gz, st, true);
+            if (e != hipSuccess) return e;
+        } else if (g.s == 2 && g.H == 2 * g.Ho && g.W == 2 * g.Wo && g.Wo % 2 == 0 &&
+                   (((uintptr_t)dz | (uintptr_t)dx) & (4 * sizeof(T) - 1)) == 0 &&
+                   (long long)N * C * g.Ho * (g.Wo / 2) < (1ll << 31)) {
+            const long long items = (long long)N * C * g.Ho * (g.Wo / 2);
+            long long blocks = (items + 255) / 256;
+            if (blocks > (1ll << 20)) blocks = 1ll << 20;
+            depthwise3x3_backward_input_s2<T><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(dz, kdw, dx, C, g, (uint32_t)items);
+            const hipError_t e = hipGetLastError();
             if (e != hipSuccess) return e;
         } else {
             const long long items = (long long)N * C * g.H * g.W;
