@@ -68,8 +68,7 @@ __global__ __launch_bounds__(256) void depthwise3x3_backward_input_s2(const T_* 
         t /= (uint32_t)G.Ho;                        // t = n*C + a
         const int a = (int)(t % (uint32_t)C);
         float k[9];
-#pragma unroll
-        for (int i = 0; i < 9; ++i) k[i] = to_f32(kdw[a * 9 + i]);
+        dw::load_taps(kdw, a, false, k);
         const T_* g0 = dz + t * HWo + (size_t)m * G.Wo + q0;
         const bool down = m + 1 < G.Ho, right = q0 + 2 < G.Wo;
         const T_* g1 = down ? g0 + G.Wo : g0;

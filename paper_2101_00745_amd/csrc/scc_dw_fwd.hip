@@ -41,16 +41,18 @@ int pow2_floor_dw(int v)
     return p;
 }
 
-// Stand-alone depthwise stage on strips (see dw_strip): stride 1 or 2 with output rows that are a multiple of 4
-// pixels, input maps of exactly S times the output size, RB dividing the output rows, tensors aligned to 4 values.
-template <typename T_, int S, int RB>
+// Stand-alone depthwise stage on strips (see scc_dw_strip.h): stride 1 or 2, input maps of exactly S times the
+// output size, RB dividing the output rows.  VEC: output rows are whole quads of pixels and the tensors are aligned
+// to 4 values (vector loads and stores); else (S == 1 only) rows of any length, a row's last strip may be partial,
+// single loads and stores.
+template <typename T_, int S, int RB, bool VEC>
 __global__ __launch_bounds__(256) void depthwise3x3_strips(const T_* __restrict__ x, const T_* __restrict__ kdw,
                                                            T_* __restrict__ z, int C, DwGeom G, long long items,
                                                            int flip)
 {
     typedef T_ tvec __attribute__((ext_vector_type(4)));
     const size_t HWi = (size_t)G.H * G.W, HWo = (size_t)G.Ho * G.Wo;
-    const uint32_t W4 = G.Wo / 4, SB = G.Ho / RB;
+    const uint32_t W4 = (G.Wo + 3) / 4, SB = G.Ho / RB;
     // 32-bit index arithmetic (the launcher sends fewer than 2^31 strips here): 64-bit divisions in every lane
     // cost more than the stencil itself.  All lanes of a wavefront run the same number of trips (the strip
     // routine shuffles between lanes); lanes past the end compute strip 0 again and store nothing.
@@ -64,41 +66,102 @@ __global__ __launch_bounds__(256) void depthwise3x3_strips(const T_* __restrict_
         const int r0 = (int)(t % SB) * RB;
         t /= SB;                          // t = n*C + a
         const int a = (int)(t % (uint32_t)C);
+        const int ncols = G.Wo - cw < 4 ? G.Wo - cw : 4;
         float k[9];
-#pragma unroll
-        for (int i = 0; i < 9; ++i) k[i] = to_f32(kdw[a * 9 + (flip ? 8 - i : i)]);   // flip: the filter turned by 180 degrees
+        dw::load_taps(kdw, a, flip != 0, k);
         const uint32_t rowmask = dw::strip_rowmask<S, RB>(r0, G.Ho);
         float out[RB][4];
         // consecutive strips of a row are consecutive lanes; the first and last lane of the wavefront and the
         // last live one have no neighbour to ask
-        dw_strip<S, RB>(x + t * HWi + (size_t)(S * r0) * G.W + S * cw, G.W, k, rowmask, cw > 0, cw + 4 < G.Wo, lane == 0,
-                        lane == 63 || ee + 1 >= (uint32_t)items, out);
+        dw_strip<S, RB, VEC>(x + t * HWi + (size_t)(S * r0) * G.W + S * cw, G.W, k, rowmask, cw > 0, cw + 4 < G.Wo,
+                             lane == 0, lane == 63 || ee + 1 >= (uint32_t)items, out, ncols);
         if (!live) continue;
         T_* zo = z + t * HWo + (size_t)r0 * G.Wo + cw;
 #pragma unroll
         for (int rr = 0; rr < RB; ++rr) {
-            tvec o;
+            if constexpr (VEC) {
+                tvec o;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) o[i] = from_f32<T_>(out[rr][i]);
-            __builtin_nontemporal_store(o, (tvec*)(zo + rr * G.Wo));
+                for (int i = 0; i < 4; ++i) o[i] = from_f32<T_>(out[rr][i]);
+                __builtin_nontemporal_store(o, (tvec*)(zo + rr * G.Wo));
+            } else {
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    if (i < ncols) __builtin_nontemporal_store(from_f32<T_>(out[rr][i]), zo + rr * G.Wo + i);
+            }
         }
     }
 }
 
+// Stand-alone depthwise stage at stride 1 for rows of any length: a thread owns ONE column of RB consecutive output
+// rows, consecutive lanes own consecutive pixels of the row-major map, so every load instruction reads consecutive
+// values; the pixels left and right of a lane's column are what its neighbouring lanes loaded (lane shuffle), and
+// each input row is loaded once per strip.  1 + 2/RB loads per output instead of the nine of the kernel below.
+template <typename T_, int RB>
+__global__ __launch_bounds__(256) void depthwise3x3_columns(const T_* __restrict__ x, const T_* __restrict__ kdw,
+                                                            T_* __restrict__ z, int C, DwGeom G, long long items,
+                                                            int flip)
+{
+    const size_t HW = (size_t)G.H * G.W;
+    const uint32_t W = (uint32_t)G.W, SB = (uint32_t)G.H / RB;
+    const uint32_t lane = threadIdx.x & 63;
+    // all lanes of a wavefront run the same number of trips (they shuffle); lanes past the end redo item 0 and store nothing
+    for (uint32_t e0 = blockIdx.x * 256u; e0 < (uint32_t)items; e0 += gridDim.x * 256u) {
+        const uint32_t ee = e0 + threadIdx.x;
+        const bool live = ee < (uint32_t)items;
+        const uint32_t e = live ? ee : 0;
+        const int c = (int)(e % W);
+        uint32_t t = e / W;
+        const int r0 = (int)(t % SB) * RB;
+        t /= SB;                          // t = n*C + a
+        float k[9];
+        dw::load_taps(kdw, (int)(t % (uint32_t)C), flip != 0, k);
+        const T_* xc = x + t * HW + (size_t)r0 * W + c;      // input pixel (r0, c)
+        const bool left = c > 0, right = c + 1 < (int)W;
+        const bool lo = lane == 0, hi = lane == 63 || ee + 1 >= (uint32_t)items;
+        float out[RB];
+#pragma unroll
+        for (int rr = 0; rr < RB; ++rr) out[rr] = 0.f;
+#pragma unroll
+        for (int tr = 0; tr < RB + 2; ++tr) {
+            const int r = r0 - 1 + tr;
+            const bool ok = r >= 0 && r < G.H;
+            const T_* row = ok ? xc + (tr - 1) * (int)W : xc;
+            const float mid = to_f32(row[0]);
+            float lv = __shfl_up(mid, 1, 64), rv = __shfl_down(mid, 1, 64);
+            if (lo && left) lv = to_f32(row[-1]);
+            if (hi && right) rv = to_f32(row[1]);
+            const float v0 = (ok && left) ? lv : 0.f, v1 = ok ? mid : 0.f, v2 = (ok && right) ? rv : 0.f;
+#pragma unroll
+            for (int rr = 0; rr < RB; ++rr) {
+                const int di = tr - rr;
+                if (di < 0 || di > 2) continue;
+                out[rr] += k[di * 3] * v0 + k[di * 3 + 1] * v1 + k[di * 3 + 2] * v2;
+            }
+        }
+        if (!live) continue;
+        T_* zo = z + t * HW + (size_t)r0 * W + c;
+#pragma unroll
+        for (int rr = 0; rr < RB; ++rr) __builtin_nontemporal_store(from_f32<T_>(out[rr]), zo + rr * (int)W);
+    }
+}
+
 // Stand-alone depthwise stage, any stride and map size: one thread per output value, taps in row-major order.
-template <typename T_>
+// IDX is the type of the flat output index: 32 bits whenever the tensor allows it (64-bit divisions in every lane
+// cost several times the stencil).
+template <typename T_, typename IDX>
 __global__ __launch_bounds__(256) void depthwise3x3_kernel(const T_* __restrict__ x, const T_* __restrict__ kdw,
                                                            T_* __restrict__ z, int C, DwGeom G, long long items,
                                                            int flip)
 {
-    const long long HWi = (long long)G.H * G.W;
-    for (long long e = (long long)blockIdx.x * 256 + threadIdx.x; e < items; e += (long long)gridDim.x * 256) {
-        const int q = (int)(e % G.Wo);
-        long long t = e / G.Wo;
-        const int m = (int)(t % G.Ho);
-        t /= G.Ho;
-        const int a = (int)(t % C);
-        const T_* xc = x + t * HWi;
+    const size_t HWi = (size_t)G.H * G.W;
+    for (IDX e = (IDX)blockIdx.x * 256 + threadIdx.x; e < (IDX)items; e += (IDX)gridDim.x * 256) {
+        const int q = (int)(e % (IDX)G.Wo);
+        IDX t = e / (IDX)G.Wo;
+        const int m = (int)(t % (IDX)G.Ho);
+        t /= (IDX)G.Ho;
+        const int a = (int)(t % (IDX)C);
+        const T_* xc = x + (size_t)t * HWi;
         float out = 0.f;
 #pragma unroll
         for (int i = 0; i < 3; ++i) {
@@ -108,7 +171,7 @@ __global__ __launch_bounds__(256) void depthwise3x3_kernel(const T_* __restrict_
             for (int j = 0; j < 3; ++j) {
                 const int cc = G.s * q + j - 1;
                 if (cc < 0 || cc >= G.W) continue;
-                out += to_f32(kdw[a * 9 + (flip ? 8 - (i * 3 + j) : i * 3 + j)]) * to_f32(xc[(long long)rr * G.W + cc]);
+                out += to_f32(kdw[a * 9 + (flip ? 8 - (i * 3 + j) : i * 3 + j)]) * to_f32(xc[(size_t)rr * G.W + cc]);
             }
         }
         z[e] = from_f32<T_>(out);
@@ -228,8 +291,7 @@ __global__ __launch_bounds__(256) void dw_scc_forward_lds(const float* __restric
 #pragma unroll 2
         for (int c = tid / IPC; c < P.Cin; c += CSTEP) {
             float k[9];
-#pragma unroll
-            for (int i = 0; i < 9; ++i) k[i] = kdw[c * 9 + i];
+            dw::load_taps(kdw, c, false, k);
             float out[RB][4];
             dw_strip<S, RB>(xb + (size_t)c * HWi, G.W, k, rowmask, left, right, false, false, out);
             float* zo = zl + ((size_t)(c >> 2) * TPP + colbase) * 4 + (c & 3);
@@ -266,8 +328,7 @@ __global__ __launch_bounds__(256) void dw_scc_forward_lds(const float* __restric
         }
         for (int c = tid / G4; c < P.Cin; c += CSTEP) {
             float k[9];
-#pragma unroll
-            for (int i = 0; i < 9; ++i) k[i] = kdw[c * 9 + i];
+            dw::load_taps(kdw, c, false, k);
             float* zo = zl + ((size_t)(c >> 2) * TPP + 4 * g4) * 4 + (c & 3);
 #pragma unroll
             for (int i4 = 0; i4 < 4; ++i4) {
@@ -431,22 +492,23 @@ hipError_t launch_fused_cp(const float* x, const float* kdw, const float* w, flo
     return rb == 4 ? launch_fused<CP, 2, 4>(x, kdw, w, y, p, g, st) : launch_fused<CP, 2, 2>(x, kdw, w, y, p, g, st);
 }
 
-template <typename T, int S>
+template <typename T, int S, bool VEC>
 hipError_t launch_strips(const T* x, const T* kdw, T* z, int N, int C, const DwGeom& g, hipStream_t st, int flip)
 {
     // taller strips read fewer halo rows per output; small problems take shorter ones to have enough threads
+    const long long w4 = (g.Wo + 3) / 4;
     int rb = g.Ho % 4 == 0 ? 4 : g.Ho % 2 == 0 ? 2 : 1;
-    while (rb > 1 && (long long)N * C * (g.Ho / rb) * (g.Wo / 4) < 256 * 1024) rb /= 2;
-    const long long items = (long long)N * C * (g.Ho / rb) * (g.Wo / 4);
+    while (rb > 1 && (long long)N * C * (g.Ho / rb) * w4 < 256 * 1024) rb /= 2;
+    const long long items = (long long)N * C * (g.Ho / rb) * w4;
     long long blocks = (items + 255) / 256;
     if (blocks > (1ll << 20)) blocks = 1ll << 20;   // the kernel strides over what is left
     const dim3 grid((unsigned)blocks), block(256);
     if (rb == 4)
-        depthwise3x3_strips<T, S, 4><<<grid, block, 0, st>>>(x, kdw, z, C, g, items, flip);
+        depthwise3x3_strips<T, S, 4, VEC><<<grid, block, 0, st>>>(x, kdw, z, C, g, items, flip);
     else if (rb == 2)
-        depthwise3x3_strips<T, S, 2><<<grid, block, 0, st>>>(x, kdw, z, C, g, items, flip);
+        depthwise3x3_strips<T, S, 2, VEC><<<grid, block, 0, st>>>(x, kdw, z, C, g, items, flip);
     else
-        depthwise3x3_strips<T, S, 1><<<grid, block, 0, st>>>(x, kdw, z, C, g, items, flip);
+        depthwise3x3_strips<T, S, 1, VEC><<<grid, block, 0, st>>>(x, kdw, z, C, g, items, flip);
     return hipGetLastError();
 }
 
@@ -455,15 +517,33 @@ hipError_t launch_strips(const T* x, const T* kdw, T* z, int N, int C, const DwG
 template <typename T>
 hipError_t launch_depthwise3x3(const T* x, const T* kdw, T* z, int N, int C, const DwGeom& g, hipStream_t st, bool flip)
 {
-    const bool strips = (g.s == 1 || g.s == 2) && g.Wo % 4 == 0 && g.H == g.s * g.Ho && g.W == g.s * g.Wo &&
-                        (((uintptr_t)x | (uintptr_t)z) & (4 * sizeof(T) - 1)) == 0 &&
-                        (long long)N * C * g.Ho * (g.Wo / 4) < (1ll << 31);
-    if (strips)
-        return g.s == 1 ? launch_strips<T, 1>(x, kdw, z, N, C, g, st, flip) : launch_strips<T, 2>(x, kdw, z, N, C, g, st, flip);
+    const bool sized = (g.s == 1 || g.s == 2) && g.H == g.s * g.Ho && g.W == g.s * g.Wo &&
+                       (long long)N * C * g.Ho * ((g.Wo + 3) / 4) < (1ll << 31);
+    const bool vec = g.Wo % 4 == 0 && (((uintptr_t)x | (uintptr_t)z) & (4 * sizeof(T) - 1)) == 0;
+    if (sized && vec)
+        return g.s == 1 ? launch_strips<T, 1, true>(x, kdw, z, N, C, g, st, flip)
+                        : launch_strips<T, 2, true>(x, kdw, z, N, C, g, st, flip);
+    if (g.s == 1 && (long long)N * C * g.H * g.W < (1ll << 31)) {       // rows of any length
+        const int rb = g.H % 4 == 0 ? 4 : g.H % 2 == 0 ? 2 : 1;
+        const long long items = (long long)N * C * (g.H / rb) * g.W;
+        long long blocks = (items + 255) / 256;
+        if (blocks > (1ll << 20)) blocks = 1ll << 20;   // the kernel strides over what is left
+        const dim3 grid((unsigned)blocks), block(256);
+        if (rb == 4)
+            depthwise3x3_columns<T, 4><<<grid, block, 0, st>>>(x, kdw, z, C, g, items, flip);
+        else if (rb == 2)
+            depthwise3x3_columns<T, 2><<<grid, block, 0, st>>>(x, kdw, z, C, g, items, flip);
+        else
+            depthwise3x3_columns<T, 1><<<grid, block, 0, st>>>(x, kdw, z, C, g, items, flip);
+        return hipGetLastError();
+    }
     const long long items = (long long)N * C * g.Ho * g.Wo;
     long long blocks = (items + 255) / 256;
     if (blocks > (1ll << 20)) blocks = 1ll << 20;
-    depthwise3x3_kernel<T><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(x, kdw, z, C, g, items, flip);
+    if (items + (1ll << 28) < (1ll << 32))      // the index plus one grid stride still fits 32 bits
+        depthwise3x3_kernel<T, uint32_t><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(x, kdw, z, C, g, items, flip);
+    else
+        depthwise3x3_kernel<T, unsigned long long><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(x, kdw, z, C, g, items, flip);
     return hipGetLastError();
 }
 

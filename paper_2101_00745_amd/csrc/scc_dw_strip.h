@@ -7,6 +7,32 @@ namespace scc {
 
 namespace dw {
 
+// The nine taps of channel a's filter as binary32, tap t of the result taking weight 8 - t when `flip` is set (the
+// filter turned by 180 degrees).  A vector memory instruction costs the same address-processing time whatever
+// its width, and the taps are a third to a half of a strip's instructions: binary32 taps are fetched with two
+// 16-byte loads and one 4-byte load (the address is only 4-byte aligned, which global loads allow).
+template <typename T_>
+__device__ __forceinline__ void load_taps(const T_* kdw, int a, bool flip, float (&k)[9])
+{
+    float raw[9];
+    if constexpr (sizeof(T_) == 4) {
+        typedef float f32x4u __attribute__((ext_vector_type(4), aligned(4)));
+        const float* src = (const float*)kdw + a * 9;
+        const f32x4u lo = *(const f32x4u*)src, hi = *(const f32x4u*)(src + 4);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            raw[i] = lo[i];
+            raw[4 + i] = hi[i];
+        }
+        raw[8] = src[8];
+    } else {
+#pragma unroll
+        for (int i = 0; i < 9; ++i) raw[i] = to_f32(kdw[a * 9 + i]);
+    }
+#pragma unroll
+    for (int i = 0; i < 9; ++i) k[i] = flip ? raw[8 - i] : raw[i];
+}
+
 // Input rows of a strip: RB consecutive output rows x 4 consecutive output columns of one channel at spatial stride
 // S (1 or 2) need NR = S*(RB-1)+3 input rows of 4*S+2 pixels each; pixel e of row t is input pixel
 // (S*r0 - 1 + t, S*cw - 1 + e).  Each row is read once: 4*S pixels from the strip's first input column on (one or
@@ -22,19 +48,30 @@ namespace dw {
 //            the edge pixel itself
 // Rows and columns outside the map are read at an address inside it and replaced by zero.  Every lane of the
 // wavefront must call this together (the shuffles are wavefront-wide).
-template <int S, typename T_>
+//   VEC      the 4*S pixels are 16-byte aligned vector loads (rows of whole quads, aligned tensors); else they are
+//            single loads and only the first `ncols` of them exist (a row's last strip may be partial; S == 1 only)
+template <int S, bool VEC = true, typename T_>
 __device__ __forceinline__ void strip_row(const T_* xc, int W, int t, uint32_t rowmask, bool left, bool right, bool lo,
-                                          bool hi, float (&v)[4 * S + 2])
+                                          bool hi, float (&v)[4 * S + 2], int ncols = 4)
 {
     typedef T_ tvec __attribute__((ext_vector_type(4)));
     const bool ok = (rowmask >> t) & 1u;
     const T_* row = ok ? xc + (t - 1) * W : xc;
     float raw[4 * S];
+    if constexpr (VEC) {
 #pragma unroll
-    for (int h = 0; h < S; ++h) {
-        const tvec m = *(const tvec*)(row + 4 * h);
+        for (int h = 0; h < S; ++h) {
+            const tvec m = *(const tvec*)(row + 4 * h);
 #pragma unroll
-        for (int e = 0; e < 4; ++e) raw[4 * h + e] = to_f32(m[e]);
+            for (int e = 0; e < 4; ++e) raw[4 * h + e] = to_f32(m[e]);
+        }
+    } else {
+        static_assert(VEC || S == 1, "partial strips are for stride 1");
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const float val = to_f32(row[e < ncols ? e : 0]);
+            raw[e] = e < ncols ? val : 0.f;
+        }
     }
     float lv = __shfl_up(raw[4 * S - 1], 1, 64);
     if (lo && left) lv = to_f32(row[-1]);
@@ -51,9 +88,9 @@ __device__ __forceinline__ void strip_row(const T_* xc, int W, int t, uint32_t r
 }
 
 // The strip's outputs: out[rr][i] = sum over taps (di, dj) of k[di*3 + dj] * pixel (S*rr + di, S*i + dj) of the rows above.
-template <int S, int RB, typename T_>
+template <int S, int RB, bool VEC = true, typename T_>
 __device__ __forceinline__ void dw_strip(const T_* xc, int W, const float (&k)[9], uint32_t rowmask, bool left, bool right,
-                                         bool lo, bool hi, float (&out)[RB][4])
+                                         bool lo, bool hi, float (&out)[RB][4], int ncols = 4)
 {
     constexpr int NR = S * (RB - 1) + 3;
 #pragma unroll
@@ -63,7 +100,7 @@ __device__ __forceinline__ void dw_strip(const T_* xc, int W, const float (&k)[9
 #pragma unroll
     for (int t = 0; t < NR; ++t) {
         float v[4 * S + 2];
-        strip_row<S>(xc, W, t, rowmask, left, right, lo, hi, v);
+        strip_row<S, VEC>(xc, W, t, rowmask, left, right, lo, hi, v, ncols);
 #pragma unroll
         for (int rr = 0; rr < RB; ++rr) {
             const int di = t - S * rr;   // tap row of output row rr that this input row feeds
