@@ -24,20 +24,24 @@ __global__ __launch_bounds__(256) void backward_merged(const T_* __restrict__ x,
                                                        float* __restrict__ out, Problem P, bwi::BwiTiling TI,
                                                        bww::BwwTiling TW, int nbww)
 {
+    // the dynamic LDS is the grad-weight range's staging area; the grad-input range, which a workgroup never is at
+    // the same time, adds its shared tiles' partial sums in it
+    extern __shared__ __attribute__((aligned(16))) float lds_dyn[];
     const int bid = (int)blockIdx.x;
     if (bid < nbww)
         bww::backward_weight_body<T_, NPT, true>(x, dy, out, P, TW, bid);
     else
-        bwi::backward_input_body<T_, CT, 8, VEC, S, 4>(dy, w, dx, P, TI, bid - nbww);
+        bwi::backward_input_body<T_, CT, 8, VEC, S, 4, true>(dy, w, dx, P, TI, bid - nbww, lds_dyn);
 }
 
 template <typename T_, int CT, bool VEC, int S, int NPT>
 hipError_t launch_variant(const T_* x, const T_* dy, const T_* w, T_* dx, float* out, const Problem& p,
                           const bwi::BwiTiling& ti, long long nbwi, const bww::BwwTiling& tw, hipStream_t st)
 {
-    constexpr size_t kLds = bww::lds_bytes_of(NPT, (int)sizeof(T_));
+    constexpr size_t kNeedW = bww::lds_bytes_of(NPT, (int)sizeof(T_)), kNeedI = bwi::reduce_bytes<CT, S, 4>();
+    constexpr size_t kLds = kNeedW > kNeedI ? kNeedW : kNeedI;
     if (kLds > 48 * 1024) {
-        // the grad-input range may add static LDS of its own; more than 64 KiB in all has to be allowed once
+        // more than 64 KiB of LDS per workgroup has to be allowed once
         static const hipError_t allowed = hipFuncSetAttribute((const void*)backward_merged<T_, CT, VEC, S, NPT>,
                                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLds);
         if (allowed != hipSuccess) return allowed;

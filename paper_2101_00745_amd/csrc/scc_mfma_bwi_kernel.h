@@ -43,10 +43,16 @@ __device__ __forceinline__ int floor_div(int a, int b)  // b > 0
 // tiles are added through LDS in slice order (layers with few columns and many covering filters).
 // WPB wavefronts per workgroup: 4, or 8 (all channel blocks of a column tile on one CU, sharing its L1) for grids
 // that fill the chip exactly once: see launch_split.
-template <typename T_, int CT, int KC, bool VEC, int S, int WPB>
+// Bytes of LDS in which the wavefronts that share a tile add their partial tiles (S > 1).
+template <int CT, int S, int WPB>
+constexpr size_t reduce_bytes() { return S > 1 ? (size_t)(WPB / S) * (S - 1) * CT * 16 * 64 * sizeof(float) : 0; }
+
+// `shared_red`: LDS of at least reduce_bytes<CT, S, WPB>() that the caller provides for that sum (a kernel that
+// holds dynamic LDS for other workgroups of its grid lends it); null: the body declares its own.
+template <typename T_, int CT, int KC, bool VEC, int S, int WPB, bool LENT = false>
 __device__ __forceinline__ void backward_input_body(const T_* __restrict__ dy, const T_* __restrict__ w,
                                                     T_* __restrict__ dx, const Problem& P, const BwiTiling& T,
-                                                    const int bid)
+                                                    const int bid, float* shared_red = nullptr)
 {
     typedef T_ bvec __attribute__((ext_vector_type(CT)));
     constexpr uint32_t ES = sizeof(T_);
@@ -189,7 +195,13 @@ __device__ __forceinline__ void backward_input_body(const T_* __restrict__ dy, c
     }
 
     if constexpr (S > 1) {   // add the slices of each tile, in slice order, into the wavefront that took slice 0
-        __shared__ float red[(S > 1 ? (WPB / S) * (S - 1) : 1) * CT * 16 * 64];
+        float* red;
+        if constexpr (LENT) {
+            red = shared_red;
+        } else {
+            __shared__ float own[(S > 1 ? (WPB / S) * (S - 1) : 1) * CT * 16 * 64];
+            red = own;
+        }
         float* mine = red + ((wave / S) * (S - 1) + (split - 1)) * (CT * 16 * 64) + lane;
         if (split > 0) {
 #pragma unroll
@@ -284,7 +296,7 @@ void select_backward_input(const T_* dy, const T_* dx, const Problem& p, F&& f)
         const long long slots = ((long long)(p.L + 31) / b.g + 1) * b.F;
         int split = 1;
         while (split < 4 && waves * split < 2048 && slots / (4 * split) >= 32) split *= 2;
-        if (CT > 1 || split == 1)     // only the narrowest tile is ever short of wavefronts
+        if (split == 1)
             with_wpb(ct, vec, integral_constant<int, 1>{});
         else if (split == 2)
             with_wpb(ct, vec, integral_constant<int, 2>{});
@@ -298,9 +310,18 @@ void select_backward_input(const T_* dy, const T_* dx, const Problem& p, F&& f)
     auto waves = [&](int ct) { return (p.NQ + 32 * ct - 1) / (32 * ct) * blocks32; };
     const uintptr_t addr = (uintptr_t)dy | (uintptr_t)dx;
     auto vec_ok = [&](int ct) { return p.HW % ct == 0 && (addr & (ct * sizeof(T_) - 1)) == 0; };
-    if (vec_ok(4) && waves(4) >= kEnoughWaves)
+    // a tile's contraction can be shared by up to 4 wavefronts (with_split): wide tiles, whose loads move 16 bytes
+    // per lane and instruction, are kept as long as that sharing still gives every SIMD a wavefront
+    auto shared = [&](long long wv) {
+        const Band b = make_band(p);
+        const long long slots = ((long long)(p.L + 31) / b.g + 1) * b.F;
+        int sp = 1;
+        while (sp < 4 && wv * sp < 2048 && slots / (4 * sp) >= 32) sp *= 2;
+        return wv * sp;
+    };
+    if (vec_ok(4) && shared(waves(4)) >= kEnoughWaves)
         with_split(integral_constant<int, 4>{}, bool_constant<true>{}, waves(4));
-    else if (vec_ok(2) && waves(2) >= kEnoughWaves)
+    else if (vec_ok(2) && shared(waves(2)) >= kEnoughWaves)
         with_split(integral_constant<int, 2>{}, bool_constant<true>{}, waves(2));
     else if (waves(2) >= kEnoughWaves)
         with_split(integral_constant<int, 2>{}, bool_constant<false>{}, waves(2));

@@ -434,16 +434,12 @@ void launch_cfg(const T_* x, const T_* w, T_* y, const Problem& p, hipStream_t s
     const FwdTiling t = filter_tiling(p);
     int split = 1;
     while (split < 4 && waves * split < 2 * kEnoughWaves && t.Uh / (2 * split) >= 32) split *= 2;
-    if constexpr (CT > 1) {       // only the narrowest tile is ever short of wavefronts
+    if (split == 1)
         launch_split<T_, CT, VEC, 1>(x, w, y, p, st);
-    } else {
-        if (split == 1)
-            launch_split<T_, CT, VEC, 1>(x, w, y, p, st);
-        else if (split == 2)
-            launch_split<T_, CT, VEC, 2>(x, w, y, p, st);
-        else
-            launch_split<T_, CT, VEC, 4>(x, w, y, p, st);
-    }
+    else if (split == 2)
+        launch_split<T_, CT, VEC, 2>(x, w, y, p, st);
+    else
+        launch_split<T_, CT, VEC, 4>(x, w, y, p, st);
 }
 
 }  // namespace
@@ -468,9 +464,16 @@ hipError_t launch_forward_mfma(const T_* x, const T_* w, T_* y, const Problem& p
     auto waves = [&](int ct) { return (p.NQ + 32 * ct - 1) / (32 * ct) * tiles; };
     const uintptr_t addr = (uintptr_t)x | (uintptr_t)y | (uintptr_t)w;
     auto vec_ok = [&](int ct) { return p.HW % ct == 0 && (addr & (ct * sizeof(T_) - 1)) == 0; };
-    if (vec_ok(4) && waves(4) >= kEnoughWaves)
+    // a tile's contraction can be shared by up to 4 wavefronts (launch_cfg): wide tiles, whose loads move 16 bytes
+    // per lane and instruction, are kept as long as that sharing still gives every SIMD a wavefront
+    auto shared = [&](long long wv) {
+        int sp = 1;
+        while (sp < 4 && wv * sp < 2 * kEnoughWaves && ft.Uh / (2 * sp) >= 32) sp *= 2;
+        return wv * sp;
+    };
+    if (vec_ok(4) && shared(waves(4)) >= kEnoughWaves)
         launch_cfg<T_, 4, true>(x, w, y, p, st, waves(4));
-    else if (vec_ok(2) && waves(2) >= kEnoughWaves)
+    else if (vec_ok(2) && shared(waves(2)) >= kEnoughWaves)
         launch_cfg<T_, 2, true>(x, w, y, p, st, waves(2));
     else if (waves(2) >= kEnoughWaves)
         launch_cfg<T_, 2, false>(x, w, y, p, st, waves(2));
