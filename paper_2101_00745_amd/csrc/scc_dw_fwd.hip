@@ -42,17 +42,15 @@ int pow2_floor_dw(int v)
 }
 
 // Stand-alone depthwise stage on strips (see scc_dw_strip.h): stride 1 or 2, input maps of exactly S times the
-// output size, RB dividing the output rows.  VEC: output rows are whole quads of pixels and the tensors are aligned
-// to 4 values (vector loads and stores); else (S == 1 only) rows of any length, a row's last strip may be partial,
-// single loads and stores.
-template <typename T_, int S, int RB, bool VEC>
+// output size, RB dividing the output rows, output rows of whole quads of pixels, tensors aligned to 4 values.
+template <typename T_, int S, int RB>
 __global__ __launch_bounds__(256) void depthwise3x3_strips(const T_* __restrict__ x, const T_* __restrict__ kdw,
                                                            T_* __restrict__ z, int C, DwGeom G, long long items,
                                                            int flip)
 {
     typedef T_ tvec __attribute__((ext_vector_type(4)));
     const size_t HWi = (size_t)G.H * G.W, HWo = (size_t)G.Ho * G.Wo;
-    const uint32_t W4 = (G.Wo + 3) / 4, SB = G.Ho / RB;
+    const uint32_t W4 = G.Wo / 4, SB = G.Ho / RB;
     // 32-bit index arithmetic (the launcher sends fewer than 2^31 strips here): 64-bit divisions in every lane
     // cost more than the stencil itself.  All lanes of a wavefront run the same number of trips (the strip
     // routine shuffles between lanes); lanes past the end compute strip 0 again and store nothing.
@@ -66,29 +64,22 @@ __global__ __launch_bounds__(256) void depthwise3x3_strips(const T_* __restrict_
         const int r0 = (int)(t % SB) * RB;
         t /= SB;                          // t = n*C + a
         const int a = (int)(t % (uint32_t)C);
-        const int ncols = G.Wo - cw < 4 ? G.Wo - cw : 4;
         float k[9];
         dw::load_taps(kdw, a, flip != 0, k);
         const uint32_t rowmask = dw::strip_rowmask<S, RB>(r0, G.Ho);
         float out[RB][4];
         // consecutive strips of a row are consecutive lanes; the first and last lane of the wavefront and the
         // last live one have no neighbour to ask
-        dw_strip<S, RB, VEC>(x + t * HWi + (size_t)(S * r0) * G.W + S * cw, G.W, k, rowmask, cw > 0, cw + 4 < G.Wo,
-                             lane == 0, lane == 63 || ee + 1 >= (uint32_t)items, out, ncols);
+        dw_strip<S, RB>(x + t * HWi + (size_t)(S * r0) * G.W + S * cw, G.W, k, rowmask, cw > 0, cw + 4 < G.Wo, lane == 0,
+                        lane == 63 || ee + 1 >= (uint32_t)items, out);
         if (!live) continue;
         T_* zo = z + t * HWo + (size_t)r0 * G.Wo + cw;
 #pragma unroll
         for (int rr = 0; rr < RB; ++rr) {
-            if constexpr (VEC) {
-                tvec o;
+            tvec o;
 #pragma unroll
-                for (int i = 0; i < 4; ++i) o[i] = from_f32<T_>(out[rr][i]);
-                __builtin_nontemporal_store(o, (tvec*)(zo + rr * G.Wo));
-            } else {
-#pragma unroll
-                for (int i = 0; i < 4; ++i)
-                    if (i < ncols) __builtin_nontemporal_store(from_f32<T_>(out[rr][i]), zo + rr * G.Wo + i);
-            }
+            for (int i = 0; i < 4; ++i) o[i] = from_f32<T_>(out[rr][i]);
+            __builtin_nontemporal_store(o, (tvec*)(zo + rr * G.Wo));
         }
     }
 }
@@ -492,11 +483,11 @@ hipError_t launch_fused_cp(const float* x, const float* kdw, const float* w, flo
     return rb == 4 ? launch_fused<CP, 2, 4>(x, kdw, w, y, p, g, st) : launch_fused<CP, 2, 2>(x, kdw, w, y, p, g, st);
 }
 
-template <typename T, int S, bool VEC>
+template <typename T, int S>
 hipError_t launch_strips(const T* x, const T* kdw, T* z, int N, int C, const DwGeom& g, hipStream_t st, int flip)
 {
     // taller strips read fewer halo rows per output; small problems take shorter ones to have enough threads
-    const long long w4 = (g.Wo + 3) / 4;
+    const long long w4 = g.Wo / 4;
     int rb = g.Ho % 4 == 0 ? 4 : g.Ho % 2 == 0 ? 2 : 1;
     while (rb > 1 && (long long)N * C * (g.Ho / rb) * w4 < 256 * 1024) rb /= 2;
     const long long items = (long long)N * C * (g.Ho / rb) * w4;
@@ -504,11 +495,11 @@ hipError_t launch_strips(const T* x, const T* kdw, T* z, int N, int C, const DwG
     if (blocks > (1ll << 20)) blocks = 1ll << 20;   // the kernel strides over what is left
     const dim3 grid((unsigned)blocks), block(256);
     if (rb == 4)
-        depthwise3x3_strips<T, S, 4, VEC><<<grid, block, 0, st>>>(x, kdw, z, C, g, items, flip);
+        depthwise3x3_strips<T, S, 4><<<grid, block, 0, st>>>(x, kdw, z, C, g, items, flip);
     else if (rb == 2)
-        depthwise3x3_strips<T, S, 2, VEC><<<grid, block, 0, st>>>(x, kdw, z, C, g, items, flip);
+        depthwise3x3_strips<T, S, 2><<<grid, block, 0, st>>>(x, kdw, z, C, g, items, flip);
     else
-        depthwise3x3_strips<T, S, 1, VEC><<<grid, block, 0, st>>>(x, kdw, z, C, g, items, flip);
+        depthwise3x3_strips<T, S, 1><<<grid, block, 0, st>>>(x, kdw, z, C, g, items, flip);
     return hipGetLastError();
 }
 
@@ -521,8 +512,7 @@ hipError_t launch_depthwise3x3(const T* x, const T* kdw, T* z, int N, int C, con
                        (long long)N * C * g.Ho * ((g.Wo + 3) / 4) < (1ll << 31);
     const bool vec = g.Wo % 4 == 0 && (((uintptr_t)x | (uintptr_t)z) & (4 * sizeof(T) - 1)) == 0;
     if (sized && vec)
-        return g.s == 1 ? launch_strips<T, 1, true>(x, kdw, z, N, C, g, st, flip)
-                        : launch_strips<T, 2, true>(x, kdw, z, N, C, g, st, flip);
+        return g.s == 1 ? launch_strips<T, 1>(x, kdw, z, N, C, g, st, flip) : launch_strips<T, 2>(x, kdw, z, N, C, g, st, flip);
     if (g.s == 1 && (long long)N * C * g.H * g.W < (1ll << 31)) {       // rows of any length
         const int rb = g.H % 4 == 0 ? 4 : g.H % 2 == 0 ? 2 : 1;
         const long long items = (long long)N * C * (g.H / rb) * g.W;

@@ -48,30 +48,19 @@ __device__ __forceinline__ void load_taps(const T_* kdw, int a, bool flip, float
 //            the edge pixel itself
 // Rows and columns outside the map are read at an address inside it and replaced by zero.  Every lane of the
 // wavefront must call this together (the shuffles are wavefront-wide).
-//   VEC      the 4*S pixels are 16-byte aligned vector loads (rows of whole quads, aligned tensors); else they are
-//            single loads and only the first `ncols` of them exist (a row's last strip may be partial; S == 1 only)
-template <int S, bool VEC = true, typename T_>
+template <int S, typename T_>
 __device__ __forceinline__ void strip_row(const T_* xc, int W, int t, uint32_t rowmask, bool left, bool right, bool lo,
-                                          bool hi, float (&v)[4 * S + 2], int ncols = 4)
+                                          bool hi, float (&v)[4 * S + 2])
 {
     typedef T_ tvec __attribute__((ext_vector_type(4)));
     const bool ok = (rowmask >> t) & 1u;
     const T_* row = ok ? xc + (t - 1) * W : xc;
     float raw[4 * S];
-    if constexpr (VEC) {
 #pragma unroll
-        for (int h = 0; h < S; ++h) {
-            const tvec m = *(const tvec*)(row + 4 * h);
+    for (int h = 0; h < S; ++h) {
+        const tvec m = *(const tvec*)(row + 4 * h);
 #pragma unroll
-            for (int e = 0; e < 4; ++e) raw[4 * h + e] = to_f32(m[e]);
-        }
-    } else {
-        static_assert(VEC || S == 1, "partial strips are for stride 1");
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const float val = to_f32(row[e < ncols ? e : 0]);
-            raw[e] = e < ncols ? val : 0.f;
-        }
+        for (int e = 0; e < 4; ++e) raw[4 * h + e] = to_f32(m[e]);
     }
     float lv = __shfl_up(raw[4 * S - 1], 1, 64);
     if (lo && left) lv = to_f32(row[-1]);
@@ -88,9 +77,9 @@ __device__ __forceinline__ void strip_row(const T_* xc, int W, int t, uint32_t r
 }
 
 // The strip's outputs: out[rr][i] = sum over taps (di, dj) of k[di*3 + dj] * pixel (S*rr + di, S*i + dj) of the rows above.
-template <int S, int RB, bool VEC = true, typename T_>
+template <int S, int RB, typename T_>
 __device__ __forceinline__ void dw_strip(const T_* xc, int W, const float (&k)[9], uint32_t rowmask, bool left, bool right,
-                                         bool lo, bool hi, float (&out)[RB][4], int ncols = 4)
+                                         bool lo, bool hi, float (&out)[RB][4])
 {
     constexpr int NR = S * (RB - 1) + 3;
 #pragma unroll
@@ -100,7 +89,7 @@ __device__ __forceinline__ void dw_strip(const T_* xc, int W, const float (&k)[9
 #pragma unroll
     for (int t = 0; t < NR; ++t) {
         float v[4 * S + 2];
-        strip_row<S, VEC>(xc, W, t, rowmask, left, right, lo, hi, v, ncols);
+        strip_row<S>(xc, W, t, rowmask, left, right, lo, hi, v);
 #pragma unroll
         for (int rr = 0; rr < RB; ++rr) {
             const int di = t - S * rr;   // tap row of output row rr that this input row feeds
