@@ -6,7 +6,8 @@
 //   dw[k,j]   = sum_{n,p} dy[n,k,p] * x[n,(s_k+j) mod Cin,p]
 //
 // Nothing about either computation changes: same tiles, same arithmetic, same summation order, so the results
-// are bitwise those of the two separate passes.  What changes is time: one launch instead of two, no drained
+// are bitwise those of the two separate passes (one exception: a split of the columns into only two slices is
+// dropped here, see bww::make_tiling, so dw is then one summation chain instead of two).  What changes is time: one launch instead of two, no drained
 // chip between them, and on layers with few columns (where each pass alone leaves most of the chip waiting on
 // latencies) the two passes overlap.  The grad-weight range comes first in the grid (its partial sums still have
 // to be reduced by a second kernel, so it should not finish last); both ranges are a multiple of 8 workgroups,
@@ -66,14 +67,14 @@ bool backward_merged_applicable(const T_* x, const T_* dy, const T_* dx, const P
     bwi::select_backward_input(dy, dx, p, [&](auto, auto, auto, auto wpb, const bwi::BwiTiling&, long long) {
         four = decltype(wpb)::value == 4;
     });
-    return four && (long long)8 * bww::make_tiling(p).chunk < (1ll << 30);
+    return four && (long long)8 * bww::make_tiling(p, true).chunk < (1ll << 30);
 }
 
 template <typename T_>
 hipError_t launch_backward_merged(const T_* x, const T_* dy, const T_* w, T_* dx, float* dw, float* workspace,
                                   const Problem& p, hipStream_t st)
 {
-    const bww::BwwTiling tw = bww::make_tiling(p);
+    const bww::BwwTiling tw = bww::make_tiling(p, true);
     float* out = tw.KS > 1 ? workspace : dw;
     hipError_t e = hipErrorInvalidValue;
     bwi::select_backward_input(dy, dx, p, [&](auto ct, auto vec, auto s, auto wpb, const bwi::BwiTiling& ti, long long nbwi) {

@@ -308,7 +308,10 @@ inline int pow2_floor(int v)
     return p;
 }
 
-inline BwwTiling make_tiling(const Problem& p)
+// side_by_side: the kernel shares its grid with the grad-input kernel (scc_backward's merged launch).  A split
+// into only two slices is then dropped: the longer main kernel hides behind the grad-input range and the reduction
+// kernel goes away (measured on the 4x4 layers of the stack: 19.7 against 22.7 us; alone it is 18 against 13.6).
+inline BwwTiling make_tiling(const Problem& p, bool side_by_side = false)
 {
     BwwTiling t;
     t.b = make_band(p);
@@ -341,6 +344,7 @@ inline BwwTiling make_tiling(const Problem& p)
     const long long ks_max = t.NQ4 / (32 * kWaves);
     if (ks > ks_max) ks = ks_max;
     if (ks < 1) ks = 1;
+    if (side_by_side && ks <= 2) ks = 1;
     t.KS = (int)ks;
     t.per_ks = (t.NQ4 + t.KS - 1) / t.KS;
     t.chunk = (int)((t.KS * tiles + 7) / 8);

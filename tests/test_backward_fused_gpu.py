@@ -106,14 +106,18 @@ def test_backward_matches_the_separate_passes_and_repeats_bitwise(S):
 @pytest.mark.parametrize("layer", OTHER[:5] + [Wk.STACK[6], Wk.STACK[11], Wk.METRIC_SWEEP[1]], ids=lambda l: l.name)
 def test_one_launch_for_both_passes_is_bitwise_the_separate_passes(S, layer, dtype):
     """Layers the fused kernel declines run the grad-weight and grad-input kernels as two ranges of one grid: same
-    tiles, same arithmetic, same summation order, so dx and dw equal those of the separate entry points bit for bit."""
+    tiles, same arithmetic, same summation order, so dx equals that of the separate entry point bit for bit, and so
+    does dw, except on layers whose columns the separate pass splits two ways: there the merged launch does not
+    split them (one summation chain instead of two), and dw agrees to rounding."""
     x, w, dy = Wk.make_inputs(layer)
     xd, wd, dyd = (torch.from_numpy(a).to(dtype).cuda() for a in (x, w, dy))
     dx1, dw1 = S.scc_backward(xd, dyd, wd, layer.cg, layer.co)
+    dx2, dw2 = S.scc_backward(xd, dyd, wd, layer.cg, layer.co)
     dxs = S.scc_backward_input(dyd, wd, layer.Cin, layer.cg, layer.co)
     dws = S.scc_backward_weight(xd, dyd, layer.cg, layer.co)
     torch.cuda.synchronize()
-    assert torch.equal(dx1, dxs) and torch.equal(dw1, dws)
+    assert torch.equal(dx1, dxs) and torch.equal(dx1, dx2) and torch.equal(dw1, dw2)
+    assert torch.equal(dw1, dws) or float((dw1 - dws).abs().max()) <= 2e-6 * float(dws.abs().max())
 
 
 def test_backward_outputs_overwritten_and_workspace_contents_do_not_matter(S):
