@@ -99,6 +99,11 @@ template <typename T> hipError_t launch_backward_weight_generic(const T* x, cons
 // Matrix-core kernels: scc_mfma_*.hip
 bool forward_mfma_eligible(const Problem& p);
 template <typename T> hipError_t launch_forward_mfma(const T* x, const T* w, T* y, const Problem& p, hipStream_t st);
+// Forward with the activation operand shared by four tiles through LDS, fp32 (scc_fwd_shared.hip)
+bool forward_shared_eligible(const float* x, const float* w, const float* y, const Problem& p);
+double forward_shared_gain(const Problem& p);   // channel fetches saved: own spans / shared walks
+bool forward_shared_preferred(const float* x, const float* w, const float* y, const Problem& p);   // ... and faster
+hipError_t launch_forward_shared(const float* x, const float* w, float* y, const Problem& p, hipStream_t st);
 bool backward_input_mfma_eligible(const Problem& p);
 template <typename T> hipError_t launch_backward_input_mfma(const T* dy, const T* w, T* dx, const Problem& p, hipStream_t st);
 bool backward_weight_mfma_eligible(const Problem& p);

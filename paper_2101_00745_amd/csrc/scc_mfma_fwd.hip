@@ -459,6 +459,10 @@ hipError_t launch_forward_mfma(const T_* x, const T_* w, T_* y, const Problem& p
     // Columns per wavefront: 128 when that still gives every SIMD a wavefront, else 64 or 32 (layers with
     // few columns and many filters).  Vector plane accesses (CT consecutive columns per lane) need planes whose
     // size is a multiple of CT and tensors aligned to the vector; otherwise a lane owns strided single columns.
+    if constexpr (sizeof(T_) == 4) {
+        if (forward_shared_preferred((const float*)x, (const float*)w, (const float*)y, p))
+            return launch_forward_shared((const float*)x, (const float*)w, (float*)y, p, st);
+    }
     const FwdTiling ft = filter_tiling(p);
     const long long tiles = (long long)ft.IB * ft.MB;
     auto waves = [&](int ct) { return (p.NQ + 32 * ct - 1) / (32 * ct) * tiles; };
