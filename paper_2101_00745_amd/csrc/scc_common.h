@@ -106,6 +106,10 @@ bool forward_shared_preferred(const float* x, const float* w, const float* y, co
 hipError_t launch_forward_shared(const float* x, const float* w, float* y, const Problem& p, hipStream_t st);
 bool backward_input_mfma_eligible(const Problem& p);
 template <typename T> hipError_t launch_backward_input_mfma(const T* dy, const T* w, T* dx, const Problem& p, hipStream_t st);
+// Grad-input with the dy operand shared by four channel blocks through LDS, fp32 (scc_bwi_shared.hip)
+bool backward_input_shared_eligible(const float* dy, const float* dx, const Problem& p);
+bool backward_input_shared_preferred(const float* dy, const float* dx, const Problem& p);   // ... and faster
+hipError_t launch_backward_input_shared(const float* dy, const float* w, float* dx, const Problem& p, hipStream_t st);
 bool backward_weight_mfma_eligible(const Problem& p);
 size_t backward_weight_mfma_workspace(const Problem& p);  // bytes of K-split partials (0 when not split)
 template <typename T>

@@ -40,6 +40,10 @@ bool backward_input_mfma_eligible(const Problem& p)
 template <typename T_>
 hipError_t launch_backward_input_mfma(const T_* dy, const T_* w, T_* dx, const Problem& p, hipStream_t st)
 {
+    if constexpr (sizeof(T_) == 4) {
+        if (backward_input_shared_preferred((const float*)dy, (const float*)dx, p))
+            return launch_backward_input_shared((const float*)dy, (const float*)w, (float*)dx, p, st);
+    }
     bwi::select_backward_input(dy, dx, p, [&](auto ct, auto vec, auto s, auto wpb, const bwi::BwiTiling& t, long long blocks) {
         constexpr int CT = decltype(ct)::value, S = decltype(s)::value, WPB = decltype(wpb)::value;
         constexpr bool VEC = decltype(vec)::value;

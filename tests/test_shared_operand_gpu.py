@@ -1,10 +1,13 @@
-"""GPU parity on layers where many 32-filter tiles read the same channels (one or two long windows with a hundred
-filters each; windows that start on every channel with a handful of filters each, as in a channel-expanding layer)
-against the fp64 CPU oracle, element by element.  The shapes are sized so that the library's forward takes the
-kernel that stages the activation operand once per workgroup of four tiles (at least 512 workgroups of 128 columns,
-four consecutive tiles reading at least three times the channels of their common walk): ragged last column tile,
-filter counts that leave tile rows and whole tiles of the last workgroup empty, walks that wrap past the last
-channel, weight rows that are and are not 16-byte aligned inside the walk.
+"""GPU parity on layers where many 32-filter tiles read the same channels, and many 32-channel blocks pull from the
+same filters (one or two long windows with a hundred filters each; windows that start on every channel with a
+handful of filters each, as in a channel-expanding layer) against the fp64 CPU oracle, element by element.
+The shapes are sized so that the library's forward and grad-input take the kernels that stage the activation
+operand once per workgroup of four tiles (at least 512 workgroups of 128 columns; four consecutive tiles reading at
+least three times the channels of their common walk, resp. four channel blocks pulling from three to four times
+the filters of their common walk): ragged last column tile, filter counts that leave tile rows and whole tiles of
+the last workgroup empty, channel counts that leave the last block and the last workgroup partly empty, walks that
+wrap past the last channel or run once around all windows, weight rows that are and are not 16-byte aligned
+inside the walk.
 Bar: max|gpu - ref| / max|ref| <= 2e-5 (the benchmark spec).
 """
 import numpy as np
@@ -39,10 +42,18 @@ SHAPES = [
 ]
 
 
+# grad-input, (N, Cin, Cout, H, W, cg, co)
+SHAPES_GRAD_INPUT = [
+    (34, 120, 250, 44, 44, 1, 0.5),     # 2 windows x 125 filters; the last channel block has 24 channels; 32 columns in the last tile
+    (33, 104, 400, 46, 44, 1, 0.3),     # 104 windows (every channel) x 4 filters, 16 of them missing: the walk is once around the circle
+    (18, 224, 448, 44, 44, 1, 0.52),    # 56 windows, 4 channels apart; 7 channel blocks: the second workgroup of a column tile holds 3
+]
+
+
 def make(cfg):
     N, Cin, Cout, H, W, cg, co = cfg
     layer = Wk.Layer("shared_n%d_c%dto%d_%dx%d_cg%d" % (N, Cin, Cout, H, W, cg), 9, N=N, Cin=Cin, Cout=Cout, H=H, W=W, cg=cg,
-                     co=co, layer=SHAPES.index(cfg))
+                     co=co, layer=(SHAPES + SHAPES_GRAD_INPUT).index(cfg))
     return Wk.make_inputs(layer)
 
 
@@ -91,3 +102,44 @@ def test_zero_weight_windows_give_exact_zeros(S):
     got = y.cpu().numpy()
     assert np.all(got[:, 1::3] == 0.0)
     assert rel_err(got, O.forward(x, w, cg, co)) <= 2e-5
+
+
+@pytest.mark.parametrize("cfg", SHAPES_GRAD_INPUT)
+def test_grad_input_every_element(S, cfg):
+    N, Cin, Cout, H, W, cg, co = cfg
+    _, w, dy = make(cfg)
+    n = N * Cin * H * W
+    buf = torch.full((n + 256,), float("nan"), device="cuda")
+    out = buf[:n].view(N, Cin, H, W)
+    S.scc_backward_input(torch.from_numpy(dy).cuda(), torch.from_numpy(w).cuda(), Cin, cg, co, out=out)
+    torch.cuda.synchronize()
+    assert not torch.isnan(out).any() and torch.isnan(buf[n:]).all()      # every element written, nothing past the end
+    assert rel_err(out.cpu().numpy(), O.backward_input(dy, w, Cin, cg, co)) <= 2e-5
+
+
+def test_grad_input_twice_is_bitwise_equal(S):
+    cfg = SHAPES_GRAD_INPUT[1]
+    N, Cin, Cout, H, W, cg, co = cfg
+    _, w, dy = make(cfg)
+    dyd, wd = torch.from_numpy(dy).cuda(), torch.from_numpy(w).cuda()
+    a = S.scc_backward_input(dyd, wd, Cin, cg, co)
+    b = S.scc_backward_input(dyd, wd, Cin, cg, co)
+    torch.cuda.synchronize()
+    assert torch.equal(a, b)
+
+
+def test_grad_input_of_zero_weight_filters_is_exact(S):
+    """With every weight zero except one filter's, dx is exactly zero outside that filter's window whatever finite
+    values dy holds, and matches the oracle inside."""
+    cfg = SHAPES_GRAD_INPUT[2]
+    N, Cin, Cout, H, W, cg, co = cfg
+    _, w, dy = make(cfg)
+    keep = 37
+    w2 = np.zeros_like(w)
+    w2[keep] = w[keep]
+    dx = S.scc_backward_input(torch.from_numpy(dy).cuda(), torch.from_numpy(w2).cuda(), Cin, cg, co)
+    torch.cuda.synchronize()
+    got = dx.cpu().numpy()
+    ref = O.backward_input(dy, w2, Cin, cg, co)
+    assert np.all(got[ref == 0.0] == 0.0)
+    assert rel_err(got, ref) <= 2e-5
