@@ -120,13 +120,21 @@ __global__ __launch_bounds__(kWavesS * 64, 2) void forward_shared32(const float*
                 ga[set][it] = *(const f32x4*)(w + (in ? srw[it] + j0 : 0));
                 gam[set] |= in ? (0xfu << (4 * it)) : 0u;
             } else {
+                // windows that start anywhere: the four weights are masked one by one, but still fetched with one
+                // 16-byte load (4-byte aligned; what it reads beside the window belongs to the same or the next
+                // filter's row) unless that load would leave the weight tensor, at its very first or last elements
+                uint32_t m4 = 0;
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const int j = j0 + q;
-                    const bool in = j >= 0 && j < P.L;
-                    ga[set][it][q] = w[in ? srw[it] + j : 0];
-                    gam[set] |= in ? (1u << (4 * it + q)) : 0u;
+                for (int q = 0; q < 4; ++q) m4 |= (j0 + q >= 0 && j0 + q < P.L) ? (1u << q) : 0u;
+                const int e0 = srw[it] + j0;
+                if (m4 == 0u || (e0 >= 0 && e0 + 4 <= P.Cout * P.L)) {
+                    typedef float f32x4u __attribute__((ext_vector_type(4), aligned(4)));
+                    ga[set][it] = *(const f32x4u*)(w + (m4 ? e0 : 0));
+                } else {
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) ga[set][it][q] = w[(m4 >> q) & 1u ? e0 + q : 0];
                 }
+                gam[set] |= m4 << (4 * it);
             }
         }
     };
