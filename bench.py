@@ -29,8 +29,8 @@ F32_MATRIX_PEAK = 157.3e12     # dense fp32 matrix peak, flop/s
 BF16_MATRIX_PEAK = 2.5e15      # dense bf16 matrix peak, flop/s
 # HBM bytes per launch on the metric layer, from two rocprofv3 --pmc runs of the build named below (FETCH_SIZE
 # scaled by the factor a plain device copy gives, WRITE_SIZE by 1.0): profiles/scc_metric_layer_kernels.md
-TRAFFIC_PROFILED_BUILD = "commit 9da5c28; profiles/scc_metric_layer_kernels.md"
-MEASURED_TRAFFIC_BYTES = {"metric": {"fwd": 67910972, "bwi": 67875991, "bww": 69266733 + 2190046, "bwd": 103423108 + 2190046}}
+TRAFFIC_PROFILED_BUILD = "commit 5274804; profiles/scc_metric_layer_kernels.md"
+MEASURED_TRAFFIC_BYTES = {"metric": {"fwd": 67910383, "bwi": 67876558, "bww": 69266705 + 2190045, "bwd": 103423085 + 2190045}}
 KERNELS = {"fwd": ["forward_mfma32"], "bwi": ["backward_input_mfma32"],
            "bww": ["backward_weight_mfma32", "backward_weight_reduce"],
            "bwd": ["backward_fused_lds32", "backward_weight_reduce"]}
