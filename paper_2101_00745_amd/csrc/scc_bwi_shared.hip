@@ -228,7 +228,7 @@ __global__ __launch_bounds__(kWavesG * 64, 2) void backward_input_shared32(const
     // barrier.  No load is conditional inside the
     // loop (a wait behind a branch that may have issued loads has to assume it did not): the loop body runs while
     // a round r+3 exists and the last rounds are written out.  The table holds a round of positions without filters
-    // past the walk, so requesting round 1 of a one-round walk stays in bounds.
+    // past the walk, so requesting the second round of a walk that has only one stays in bounds.
     typedef std::integral_constant<int, 0> Set0;
     typedef std::integral_constant<int, 1> Set1;
     auto body = [&](auto PAR, auto OTHER, int r, auto ISSUE, auto COMMIT) {

@@ -256,7 +256,7 @@ __global__ __launch_bounds__(kWavesS * 64, 2) void forward_shared32(const float*
     const std::false_type no;
     issue_a(Set0(), 0);
     issue_b(Set0());
-    issue_a(Set1(), 1);                                        // harmless when there is no round 1: in bounds, never parked
+    issue_a(Set1(), 1);                                        // harmless when the walk has a single round: in bounds, never parked
     issue_b(Set1());
     if (round_active(0)) commit_a(Set0());
     commit_b(Set0());
