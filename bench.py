@@ -422,6 +422,15 @@ def main():
                 "per_pass_GBs": {k: round(alg[k] / (v * 1e-3) / 1e9, 1) for k, v in per_pass.items()},
                 "per_pass_TFLOPs": {k: round(flops[k] * Wk.algorithmic_flops(layer) / (v * 1e-3) / 1e12, 2)
                                     for k, v in per_pass.items()}}
+    if dominant == "bwd":
+        # scc_backward performs two passes of the metric in one call and has to read dy only once: `frac` above prices
+        # it by the bytes that call must move; by the metric's own accounting (each pass's tensors once per pass, as in
+        # `value`) the same time is worth the bytes of grad-input plus grad-weight
+        by_pass = alg["bwi"] + alg["bww"]
+        roofline["by_the_metrics_per_pass_accounting"] = {
+            "algorithmic_bytes": by_pass, "GBs": round(by_pass / (per_pass["bwd"] * 1e-3) / 1e9, 1),
+            "frac": round(by_pass / (per_pass["bwd"] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+            "note": "grad-input + grad-weight counted as two passes (dy once per pass); not the call's real traffic"}
 
     out = {"metric": "SCC fwd+bwd GB/s & fraction of HBM peak, N=128 Cin=Cout=256 16x16 fp32",
            "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": K, "warmup": W,
